@@ -1,0 +1,180 @@
+/* tslt.h -- C ABI of the MI355X (gfx950) hot path of Truncated Sparse Logits Transmission.
+ *
+ * The operations are the per-position probability steps of the paper "Fast Collaborative Inference
+ * via Distributed Speculative Decoding":
+ *   device side  -- truncated sampling on the draft logits (Section 3.1: Top-K, Top-rho, the
+ *                   renormalisation equation) and "sparsify-then-sample" (Solution 1, Section 3.2);
+ *   server side  -- token-sequence verification (Algorithm 3), multi-candidate verification
+ *                   (Algorithm 5 and its residual-update equation) and token-tree verification with
+ *                   the new-sequence search (Algorithm 8; tree layout of Section 4.1).
+ *
+ * Conventions that hold for every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller unless it is marked "host".  The library
+ *     allocates nothing: scratch memory comes from a caller-provided workspace sized by
+ *     tslt_workspace_bytes() and aligned to 256 bytes.
+ *   - `stream` is a hipStream_t passed as void*.  Calls enqueue kernels on it and return without
+ *     synchronising; outputs are valid once the stream has reached that point.
+ *   - Return value: TSLT_OK, or a negative code for an error found on the host (bad argument,
+ *     workspace too small, launch failure).  Nothing is enqueued when a negative code is returned.
+ *     tslt_last_error() gives a message for the calling thread.
+ *   - Data-dependent problems never abort.  They set bits in the optional per-row / per-sequence
+ *     `status` array (TSLT_ROW_*) and give the defined fallback (count 0, token -1).
+ *   - Logit rows are row-major with `row_stride` elements between rows; any alignment of the element
+ *     type is accepted.  dtype is fp32 or bf16 (bf16 is widened exactly to fp32 on load).
+ *   - Temperature (not in the paper): s = fl32(z * fl32(1/T)), one fp32 multiplication per logit.
+ *     The SCALED values are what a truncated set carries, so the server needs no draft-side
+ *     parameter: q_hat is the plain softmax of the received values.  T must be > 0.
+ *   - Order of a truncated set ("canonical order"): raw logit descending, ties by ascending token
+ *     index.  Logits equal to -inf have probability 0 and are never selected; NaN or +inf marks the
+ *     row TSLT_ROW_NONFINITE.
+ *   - Sampling is inverse-CDF with caller-supplied uniforms u in [0,1): the first bucket whose
+ *     cumulative weight exceeds u * total, accumulated in fp64.  Dense distributions are scanned in
+ *     ascending token index, sparse ones in canonical order.  Uniforms are indexed by position /
+ *     node, never by control flow, so results do not depend on evaluation order.
+ */
+#ifndef TSLT_H
+#define TSLT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { TSLT_F32 = 0, TSLT_BF16 = 1 } tslt_dtype;
+
+enum {
+  TSLT_OK = 0,
+  TSLT_ERR_INVALID_ARG = -1,
+  TSLT_ERR_UNSUPPORTED = -2,  /* a size beyond what the kernels are built for (see TSLT_MAX_K_CAP) */
+  TSLT_ERR_WORKSPACE = -3,    /* workspace missing, misaligned or smaller than tslt_workspace_bytes() */
+  TSLT_ERR_HIP = -4           /* a HIP runtime call failed */
+};
+
+/* bits of the per-row / per-sequence status words */
+enum {
+  TSLT_ROW_NONFINITE = 1,        /* NaN or +inf among the logits of a row that was needed */
+  TSLT_ROW_EMPTY = 2,            /* no logit above -inf, or an empty sparse set */
+  TSLT_ROW_TOKEN_NOT_IN_SET = 4, /* a draft token / candidate that is not in its sparse set: rejected */
+  TSLT_ROW_EXACT_PATH = 256      /* informational: the row took the multi-pass selection path */
+};
+
+enum { TSLT_OP_TRUNCATE = 0, TSLT_OP_SAMPLE = 1, TSLT_OP_VERIFY = 2, TSLT_OP_VERIFY_TREE = 3 };
+
+#define TSLT_MAX_K_CAP 1024   /* largest width of a sparse set */
+#define TSLT_MAX_TREE_DEPTH 16
+#define TSLT_MAX_BRANCH 16    /* largest k_l of an expansion configuration */
+
+/* Library version (major*10000 + minor*100 + patch). */
+int tslt_version(void);
+
+/* Message of the last error returned to the calling thread ("" if none).  Host pointer, valid until
+ * the next failing call on this thread. */
+const char* tslt_last_error(void);
+
+/* Bytes of workspace an operation needs.  `n_outer` is the number of rows (truncate, sample) or of
+ * sequences B (verify, verify_tree); `n_inner` is gamma (verify) or N_nodes (verify_tree), ignored
+ * otherwise.  Returns 0 when the operation needs none. */
+size_t tslt_workspace_bytes(int op, int64_t n_outer, int64_t n_inner, int64_t V, int32_t k_cap);
+
+/* Truncated sampling on logits (Section 3.1; Solution 1 of Section 3.2), one draft row per position.
+ *
+ *   logits      [rows, row_stride] draft logits z
+ *   temperature T > 0
+ *   top_k       K of Top-K; 0 = off.  Effective selection size is min(K, k_cap, #logits > -inf)
+ *   top_p       rho of Top-rho in (0,1); 0 or >= 1 = off.  The kept set is the smallest prefix of the
+ *               canonical order whose mass, measured against the FULL-vocabulary normaliser, is
+ *               >= rho; it is cut at the selection size above without changing that test
+ *   k_cap       width of the outputs, 1..TSLT_MAX_K_CAP
+ *   out_idx     [rows, k_cap] int32 token ids in canonical order; -1 beyond count
+ *   out_logit   [rows, k_cap] fp32 scaled logits s of the kept tokens (the payload); -inf beyond count
+ *   out_prob    [rows, k_cap] fp32 q_hat = q / sum_{kept} q (renormalisation equation); 0 beyond
+ *               count; may be NULL
+ *   out_count   [rows] int32 size of the kept set
+ *   out_mass    [rows] fp32 rho-mass of the kept set, sum_{kept} q (sigma of Theorem 1 = 1 - mass);
+ *               may be NULL
+ *   status      [rows] int32 TSLT_ROW_* bits (written, not accumulated); may be NULL
+ * Workspace: none (ws may be NULL).
+ */
+int tslt_truncate(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
+                  float temperature, int32_t top_k, float top_p, int32_t k_cap,
+                  int32_t* out_idx, float* out_logit, float* out_prob, int32_t* out_count,
+                  float* out_mass, int32_t* status, void* ws, size_t ws_bytes, void* stream);
+
+/* Sample from truncated distributions (the sample step of Algorithm 2; Algorithm 4 for k candidates).
+ *
+ *   idx, logit, count   a truncated set per row as written by tslt_truncate ([rows, k_cap], [rows])
+ *   u                   [rows, n_samples] fp32 uniforms in [0,1)
+ *   without_replacement 0: the n_samples draws are i.i.d. from q_hat (Algorithm 4);
+ *                       1: each drawn slot is removed and the rest renormalised before the next draw
+ *   out_token           [rows, n_samples] int32 sampled token ids (-1 if the set is empty or exhausted)
+ *   out_slot            [rows, n_samples] int32 position of the token inside its set; may be NULL
+ * Workspace: none.
+ */
+int tslt_sample(const int32_t* idx, const float* logit, const int32_t* count, int64_t rows,
+                int32_t k_cap, const float* u, int32_t n_samples, int32_t without_replacement,
+                int32_t* out_token, int32_t* out_slot, void* stream);
+
+/* Token-sequence verification (Algorithm 3) for B sequences of gamma draft positions.
+ *
+ *   target_logits [B, gamma+1, row_stride] target logits; row gamma is the bonus row P_{L+1}
+ *   target_temperature  T_p > 0 applied to the target rows as in tslt_truncate
+ *   q_idx, q_logit [B, gamma, k_cap], q_count [B, gamma]  the received truncated sets
+ *   draft_tokens  [B, gamma] int32 the drafted x_j
+ *   u_accept      [B, gamma], u_resample [B, gamma+1] fp32 uniforms in [0,1)
+ *   out_accept_len [B] int32 number of accepted draft tokens n in 0..gamma: x_j is accepted iff
+ *                 u_accept[j] < min(1, p_j(x_j) / q_hat_j(x_j)) and every earlier one was
+ *   out_tokens    [B, gamma+1] int32: the n accepted tokens, then the token resampled from
+ *                 norm(max(0, p - q_hat)) at the first rejected position (uniform u_resample[n]), or,
+ *                 if n = gamma, the bonus token drawn from p_{gamma+1} (u_resample[gamma]); -1 after
+ *   out_ratio     [B, gamma] fp32 p/q_hat for every position (all are evaluated, as the algorithm
+ *                 verifies in parallel); -1 where the token is not in its set; may be NULL
+ *   out_beta      [B, gamma] fp32 sum_x min(q_hat, p) per position (Lemma 1's acceptance rate); may
+ *                 be NULL
+ *   status        [B] int32; may be NULL
+ * Workspace: tslt_workspace_bytes(TSLT_OP_VERIFY, B, gamma, V, k_cap).
+ */
+int tslt_verify(const void* target_logits, tslt_dtype dt, int64_t B, int32_t gamma, int64_t V,
+                int64_t row_stride, float target_temperature,
+                const int32_t* q_idx, const float* q_logit, const int32_t* q_count, int32_t k_cap,
+                const int32_t* draft_tokens, const float* u_accept, const float* u_resample,
+                int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta,
+                int32_t* status, void* ws, size_t ws_bytes, void* stream);
+
+/* Token-tree verification (Algorithm 8 with Algorithm 5 at every non-leaf node) for B trees.
+ *
+ * Nodes are stored breadth-first (Section 4.1): layer l has W_l = k_1*...*k_l nodes, the i-th node of
+ * layer l (0-based) owns nodes i*k_{l+1} .. (i+1)*k_{l+1}-1 of layer l+1.  N_nodes = sum_l W_l,
+ * N_int = N_nodes - W_L.
+ *
+ *   target_logits [B, N_nodes, row_stride] target logits of every node
+ *   depth, expansion   L and the HOST array k_1..k_L (1 <= k_l <= TSLT_MAX_BRANCH)
+ *   q_idx, q_logit [B, N_int, k_cap], q_count [B, N_int]  truncated draft set of every non-leaf node
+ *   cand_tokens   [B, N_nodes-1] int32: entry n-1 is the token of node n (n >= 1); -1 = absent
+ *   u_accept      [B, N_nodes-1] fp32 one uniform per candidate node (entry n-1 for node n)
+ *   u_resample    [B, N_nodes] fp32 one uniform per node
+ *   out_node_token, out_node_slot [B, N_nodes] int32: output of every node -- for a non-leaf node the
+ *                 accepted candidate and its child number 0..k-1, or, after k rejections, a sample of
+ *                 P^(k+1) (p^(i+1) = norm(max(0, p^(i) - q_hat)), same q_hat at every step) and -1;
+ *                 for a leaf a sample of its target distribution and -1.  Both may be NULL: then only
+ *                 the nodes on the verified path are evaluated.
+ *   out_seq       [B, depth+1] int32 verified sequence: walk from the root, append the node's output,
+ *                 descend into the accepted child, stop at the first node without one; -1 after
+ *   out_len       [B] int32 length of that sequence, 1..depth+1
+ *   out_ratio     [B, N_nodes-1] fp32 p^(i)/q_hat of every candidate that was tested (NaN if an
+ *                 earlier sibling was accepted first, -1 if not in the set); may be NULL
+ *   status        [B] int32; may be NULL
+ * Workspace: tslt_workspace_bytes(TSLT_OP_VERIFY_TREE, B, N_nodes, V, k_cap).
+ */
+int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_t V, int64_t row_stride,
+                     float target_temperature, int32_t depth, const int32_t* expansion,
+                     const int32_t* q_idx, const float* q_logit, const int32_t* q_count, int32_t k_cap,
+                     const int32_t* cand_tokens, const float* u_accept, const float* u_resample,
+                     int32_t* out_node_token, int32_t* out_node_slot, int32_t* out_seq, int32_t* out_len,
+                     float* out_ratio, int32_t* status, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSLT_H */

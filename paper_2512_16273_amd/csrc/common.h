@@ -1,0 +1,271 @@
+// Device-side helpers shared by the TSLT kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tslt {
+
+constexpr int kBlock = 256;            // threads per workgroup of the streaming kernels
+constexpr int kWaves = kBlock / 64;
+constexpr uint32_t kNegInfBits = 0xFF800000u;
+
+struct Bf16 { uint16_t bits; };        // storage tag for bf16 rows
+
+template <typename T> struct ElemTraits;
+template <> struct ElemTraits<float> {
+  static constexpr int kPerVec = 4;    // elements per 16-byte vector
+  static constexpr int kBytes = 4;
+};
+template <> struct ElemTraits<Bf16> {
+  static constexpr int kPerVec = 8;
+  static constexpr int kBytes = 2;
+};
+
+__device__ __forceinline__ float as_f32(uint32_t b) { return __uint_as_float(b); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __float_as_uint(f); }
+
+// Element i of a 16-byte vector, widened exactly to fp32.
+template <typename T> __device__ __forceinline__ void unpack(const uint4& w, float (&v)[ElemTraits<T>::kPerVec]);
+template <> __device__ __forceinline__ void unpack<float>(const uint4& w, float (&v)[4]) {
+  v[0] = as_f32(w.x); v[1] = as_f32(w.y); v[2] = as_f32(w.z); v[3] = as_f32(w.w);
+}
+template <> __device__ __forceinline__ void unpack<Bf16>(const uint4& w, float (&v)[8]) {
+  v[0] = as_f32(w.x << 16); v[1] = as_f32(w.x & 0xFFFF0000u);
+  v[2] = as_f32(w.y << 16); v[3] = as_f32(w.y & 0xFFFF0000u);
+  v[4] = as_f32(w.z << 16); v[5] = as_f32(w.z & 0xFFFF0000u);
+  v[6] = as_f32(w.w << 16); v[7] = as_f32(w.w & 0xFFFF0000u);
+}
+
+template <typename T> __device__ __forceinline__ uint4 neg_inf_vec();
+template <> __device__ __forceinline__ uint4 neg_inf_vec<float>() {
+  return make_uint4(kNegInfBits, kNegInfBits, kNegInfBits, kNegInfBits);
+}
+template <> __device__ __forceinline__ uint4 neg_inf_vec<Bf16>() {
+  return make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u);
+}
+
+// Scalar load of element i of a row, any alignment of the element type.
+template <typename T> __device__ __forceinline__ float load_elem(const void* row, int64_t i);
+template <> __device__ __forceinline__ float load_elem<float>(const void* row, int64_t i) {
+  return reinterpret_cast<const float*>(row)[i];
+}
+template <> __device__ __forceinline__ float load_elem<Bf16>(const void* row, int64_t i) {
+  return as_f32(uint32_t(reinterpret_cast<const uint16_t*>(row)[i]) << 16);
+}
+
+// Order-preserving map fp32 -> uint32 (larger value, larger key).  -0.0 must be folded into +0.0 by
+// the caller (add 0.0f) when the two have to compare equal.
+__device__ __forceinline__ uint32_t mono_key(float v) {
+  uint32_t b = as_u32(v);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key_to_f32(uint32_t k) {
+  return as_f32((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+constexpr uint32_t kKeyNegInf = 0x007FFFFFu;   // mono_key(-inf)
+constexpr uint32_t kKeyPosInf = 0xFF800000u;   // mono_key(+inf)
+
+// Candidate record: value key in the high word, inverted index in the low word, so that a plain
+// descending sort of the 64-bit word gives "value descending, index ascending".
+__device__ __forceinline__ uint64_t make_cand(float v, uint32_t idx) {
+  return (uint64_t(mono_key(v + 0.0f)) << 32) | uint64_t(0xFFFFFFFFu - idx);
+}
+__device__ __forceinline__ float cand_value(uint64_t c) { return key_to_f32(uint32_t(c >> 32)); }
+__device__ __forceinline__ uint32_t cand_index(uint64_t c) { return 0xFFFFFFFFu - uint32_t(c); }
+
+// 16-byte streaming load (read-once data: do not keep it in the caches longer than needed).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_vec_stream(const uint4* p) {
+  u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(r.x, r.y, r.z, r.w);
+}
+__device__ __forceinline__ uint4 load_vec(const uint4* p) {
+  u32x4_t r = *reinterpret_cast<const u32x4_t*>(p);
+  return make_uint4(r.x, r.y, r.z, r.w);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+__device__ __forceinline__ uint64_t ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+__device__ __forceinline__ int lanes_below(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi(uint32_t(mask >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(mask), 0));
+}
+
+__device__ __forceinline__ double shfl_xor_f64(double v, int m) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __shfl_xor(lo, m, 64); hi = __shfl_xor(hi, m, 64);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double shfl_up_f64(double v, int d) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __shfl_up(lo, d, 64); hi = __shfl_up(hi, d, 64);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double shfl_f64(double v, int src) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __shfl(lo, src, 64); hi = __shfl(hi, src, 64);
+  return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) v += shfl_xor_f64(v, m);
+  return v;
+}
+__device__ __forceinline__ float wave_max_f32(float v) {
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) {
+    uint32_t o = uint32_t(__shfl_xor(int(v), m, 64));
+    v = o > v ? o : v;
+  }
+  return v;
+}
+__device__ __forceinline__ int wave_sum_i32(int v) {
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+
+// Small per-block scratch for reductions and scans; one instance lives in static LDS.
+// `NW` is the number of waves of the workgroup that calls the helpers.
+struct BlockScratch {
+  double d[16];
+  float f[16];
+  int i[16];
+};
+
+// Block-wide reductions.  Every thread of the block must call; the result is returned to all.
+template <int NW> __device__ __forceinline__ double block_sum_f64(double v, BlockScratch& s) {
+  v = wave_sum_f64(v);
+  __syncthreads();
+  if (lane_id() == 0) s.d[wave_id()] = v;
+  __syncthreads();
+  double t = 0.0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) t += s.d[w];
+  return t;
+}
+template <int NW> __device__ __forceinline__ float block_max_f32(float v, BlockScratch& s) {
+  v = wave_max_f32(v);
+  __syncthreads();
+  if (lane_id() == 0) s.f[wave_id()] = v;
+  __syncthreads();
+  float t = s.f[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) t = fmaxf(t, s.f[w]);
+  return t;
+}
+template <int NW> __device__ __forceinline__ int block_sum_i32(int v, BlockScratch& s) {
+  v = wave_sum_i32(v);
+  __syncthreads();
+  if (lane_id() == 0) s.i[wave_id()] = v;
+  __syncthreads();
+  int t = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) t += s.i[w];
+  return t;
+}
+
+template <int NW> __device__ __forceinline__ int block_or_i32(int v, BlockScratch& s) {
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) v |= __shfl_xor(v, m, 64);
+  __syncthreads();
+  if (lane_id() == 0) s.i[wave_id()] = v;
+  __syncthreads();
+  int t = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) t |= s.i[w];
+  return t;
+}
+
+// Block-wide exclusive scans in thread order; `total` receives the sum over the block.
+template <int NW> __device__ __forceinline__ double block_excl_scan_f64(double v, BlockScratch& s, double& total) {
+  double inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    double up = shfl_up_f64(inc, d);
+    if (lane_id() >= d) inc += up;
+  }
+  __syncthreads();
+  if (lane_id() == 63) s.d[wave_id()] = inc;
+  __syncthreads();
+  double base = 0.0, t = 0.0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    if (w < wave_id()) base += s.d[w];
+    t += s.d[w];
+  }
+  total = t;
+  return base + inc - v;
+}
+template <int NW> __device__ __forceinline__ int block_excl_scan_i32(int v, BlockScratch& s, int& total) {
+  int inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    int up = __shfl_up(inc, d, 64);
+    if (lane_id() >= d) inc += up;
+  }
+  __syncthreads();
+  if (lane_id() == 63) s.i[wave_id()] = inc;
+  __syncthreads();
+  int base = 0, t = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    if (w < wave_id()) base += s.i[w];
+    t += s.i[w];
+  }
+  total = t;
+  return base + inc - v;
+}
+
+// In-LDS bitonic sort, descending, of n (a power of two) 64-bit words by `nthreads` threads.
+__device__ __forceinline__ void bitonic_sort_desc(uint64_t* a, int n, int tid, int nthreads) {
+  for (int k = 2; k <= n; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int p = tid; p < (n >> 1); p += nthreads) {
+        int lo = ((p & ~(j - 1)) << 1) | (p & (j - 1));
+        int hi = lo | j;
+        bool desc = (lo & k) == 0;
+        uint64_t x = a[lo], y = a[hi];
+        if ((x < y) == desc) { a[lo] = y; a[hi] = x; }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// How a row of V elements splits into a 16-byte aligned body of whole vectors plus at most
+// 2*(kPerVec-1) edge elements in front of and behind it.
+struct RowSplit {
+  int head;        // elements before the aligned body
+  int64_t nvec;    // whole 16-byte vectors in the body
+  int tail;        // elements after the body
+  const uint4* body;
+};
+template <typename T> __device__ __forceinline__ RowSplit split_row(const void* row, int64_t V) {
+  constexpr int E = ElemTraits<T>::kPerVec;
+  RowSplit r;
+  uintptr_t a = reinterpret_cast<uintptr_t>(row);
+  int mis = int((a & 15u) / ElemTraits<T>::kBytes);
+  int head = mis ? (E - mis) : 0;
+  if (head > V) head = int(V);
+  r.head = head;
+  r.nvec = (V - head) / E;
+  r.tail = int(V - head - r.nvec * E);
+  r.body = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(row) + size_t(head) * ElemTraits<T>::kBytes);
+  return r;
+}
+// Index (within the row) and value of edge element e in 0 .. head+tail-1.
+template <typename T> __device__ __forceinline__ int64_t edge_index(const RowSplit& r, int e) {
+  return e < r.head ? int64_t(e) : int64_t(r.head) + r.nvec * ElemTraits<T>::kPerVec + (e - r.head);
+}
+
+}  // namespace tslt

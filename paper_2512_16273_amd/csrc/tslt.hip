@@ -1,0 +1,210 @@
+// C ABI of the TSLT hot path (see include/tslt.h): argument checks, launch plans, kernel launches.
+#include "tslt.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <string>
+
+#include "common.h"
+#include "sample.h"
+#include "truncate.h"
+#include "verify.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+  return fail(TSLT_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool valid_dtype(tslt_dtype dt) { return dt == TSLT_F32 || dt == TSLT_BF16; }
+
+// fl32(1/T), the one scaling constant every side derives the same way
+float reciprocal_temperature(float T) { return float(1.0 / double(T)); }
+float log2e_over_T(float rT) { return float(double(rT) * 1.4426950408889634074); }
+
+constexpr size_t kMaxLds = 160 * 1024;   // LDS of one gfx950 compute unit
+
+int next_pow2(int v) {
+  int p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+// Launch plan of the truncate kernel: which rank among the per-thread sample maxima gives the
+// threshold, and how large the hit buffers and the candidate array have to be.
+size_t plan_truncate(tslt_dtype dt, int64_t V, tslt::TruncateParams& p) {
+  const int E = dt == TSLT_BF16 ? 8 : 4;
+  const double G = tslt::kBlock;
+  const int64_t tile = int64_t(tslt::kBlock) * E;
+  const int64_t n_tiles = (V + tile - 1) / tile;
+  const int64_t ns = n_tiles < tslt::kSampleTiles ? n_tiles : tslt::kSampleTiles;
+  const double n_sample = double(ns * tile < V ? ns * tile : V);
+  const double f = n_sample / double(V);
+  const double kp = p.k_sel * f;                       // expected sample elements inside the top-k
+  const double j = f >= 1.0 ? kp + 1.0 : kp + 4.0 * std::sqrt(kp) + 4.0;
+  const double jc = G * (1.0 - std::exp(-j / G));      // distinct threads holding the top j
+  int jprime = int(std::ceil(jc + 2.0 * std::sqrt(j > jc ? j - jc : 0.0) + 1.0));
+  p.tau_bits = dt == TSLT_BF16 ? 16 : 20;
+  p.jprime = 0;
+  p.wave_cap = 1;
+  p.sort_cap = next_pow2(p.k_sel < 64 ? 64 : p.k_sel);
+  if (jprime <= int(0.8 * G)) {
+    const double j_eff = -G * std::log(1.0 - double(jprime) / G);
+    const double cap_total = (j_eff + 4.0 * std::sqrt(j_eff) + 8.0) / f * 1.05;
+    const int wave_cap = int(std::ceil(cap_total / tslt::kWaves * 1.3)) + 16;
+    int sort_cap = next_pow2(int(cap_total * 1.1) + 1);
+    if (sort_cap < p.sort_cap) sort_cap = p.sort_cap;
+    const size_t lds = size_t(20) * tslt::kWaves * wave_cap + 8 + size_t(8) * sort_cap;
+    if (lds + sizeof(tslt::TruncateShared) + 256 <= kMaxLds) {
+      p.jprime = jprime;
+      p.wave_cap = wave_cap;
+      p.sort_cap = sort_cap;
+    }
+  }
+  return size_t(20) * tslt::kWaves * p.wave_cap + 8 + size_t(8) * p.sort_cap;
+}
+
+template <typename K> hipError_t allow_large_lds(K kernel) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             int(kMaxLds - 4096));
+}
+
+}  // namespace
+
+extern "C" {
+
+int tslt_version(void) { return 100; }
+
+const char* tslt_last_error(void) { return g_last_error.c_str(); }
+
+size_t tslt_workspace_bytes(int op, int64_t n_outer, int64_t n_inner, int64_t V, int32_t k_cap) {
+  if (n_outer <= 0 || V <= 0) return 0;
+  switch (op) {
+    case TSLT_OP_VERIFY:
+      return tslt::verify_workspace_bytes(n_outer, n_inner, V, k_cap);
+    default:
+      return 0;
+  }
+}
+
+int tslt_truncate(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
+                  float temperature, int32_t top_k, float top_p, int32_t k_cap, int32_t* out_idx,
+                  float* out_logit, float* out_prob, int32_t* out_count, float* out_mass, int32_t* status,
+                  void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: unknown dtype %d", int(dt));
+  if (rows < 0 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: bad shape rows=%lld V=%lld stride=%lld", (long long)rows, (long long)V, (long long)row_stride);
+  if (V > 0x7FFFFFFF || rows > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "tslt_truncate: V and rows must fit 31 bits");
+  if (!(temperature > 0.0f) || !std::isfinite(temperature)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: temperature must be > 0");
+  if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "tslt_truncate: k_cap must be in 1..%d", TSLT_MAX_K_CAP);
+  if (top_k < 0 || !(top_p >= 0.0f)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: top_k and top_p must be >= 0");
+  if (rows == 0) return TSLT_OK;
+  if (!logits || !out_idx || !out_logit || !out_count) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: null pointer");
+  if (reinterpret_cast<uintptr_t>(logits) % (dt == TSLT_BF16 ? 2 : 4)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: logits not aligned to their element type");
+
+  tslt::TruncateParams p{};
+  p.logits = logits; p.rows = rows; p.V = V; p.row_stride = row_stride;
+  p.rT = reciprocal_temperature(temperature);
+  p.k2 = log2e_over_T(p.rT);
+  p.top_p = (top_p > 0.0f && top_p < 1.0f) ? top_p : 0.0f;
+  p.k_cap = k_cap;
+  p.k_sel = (top_k > 0 && top_k < k_cap) ? top_k : k_cap;
+  p.out_idx = out_idx; p.out_logit = out_logit; p.out_prob = out_prob; p.out_count = out_count;
+  p.out_mass = out_mass; p.status = status;
+  const size_t lds = plan_truncate(dt, V, p);
+
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  hipError_t e;
+  const bool big_lds = lds + sizeof(tslt::TruncateShared) > 48 * 1024;
+  if (dt == TSLT_BF16) {
+    if (big_lds && (e = allow_large_lds(tslt::truncate_kernel<tslt::Bf16>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    hipLaunchKernelGGL(tslt::truncate_kernel<tslt::Bf16>, dim3(unsigned(rows)), dim3(tslt::kBlock), lds, s, p);
+  } else {
+    if (big_lds && (e = allow_large_lds(tslt::truncate_kernel<float>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    hipLaunchKernelGGL(tslt::truncate_kernel<float>, dim3(unsigned(rows)), dim3(tslt::kBlock), lds, s, p);
+  }
+  if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "tslt_truncate launch");
+  return TSLT_OK;
+}
+
+int tslt_sample(const int32_t* idx, const float* logit, const int32_t* count, int64_t rows, int32_t k_cap,
+                const float* u, int32_t n_samples, int32_t without_replacement, int32_t* out_token,
+                int32_t* out_slot, void* stream) {
+  if (rows < 0 || rows > 0x7FFFFFFF) return fail(TSLT_ERR_INVALID_ARG, "tslt_sample: bad row count");
+  if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "tslt_sample: k_cap must be in 1..%d", TSLT_MAX_K_CAP);
+  if (n_samples < 0) return fail(TSLT_ERR_INVALID_ARG, "tslt_sample: n_samples < 0");
+  if (rows == 0 || n_samples == 0) return TSLT_OK;
+  if (!idx || !logit || !count || !u || !out_token) return fail(TSLT_ERR_INVALID_ARG, "tslt_sample: null pointer");
+  tslt::SampleParams p{idx, logit, count, rows, k_cap, u, n_samples, without_replacement ? 1 : 0, out_token, out_slot};
+  hipLaunchKernelGGL(tslt::sample_kernel, dim3(unsigned(rows)), dim3(64), 0, reinterpret_cast<hipStream_t>(stream), p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e, "tslt_sample launch");
+  return TSLT_OK;
+}
+
+int tslt_verify(const void* target_logits, tslt_dtype dt, int64_t B, int32_t gamma, int64_t V, int64_t row_stride,
+                float target_temperature, const int32_t* q_idx, const float* q_logit, const int32_t* q_count,
+                int32_t k_cap, const int32_t* draft_tokens, const float* u_accept, const float* u_resample,
+                int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta, int32_t* status,
+                void* ws, size_t ws_bytes, void* stream) {
+  if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "tslt_verify: unknown dtype %d", int(dt));
+  if (B < 0 || gamma < 1 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "tslt_verify: bad shape");
+  if (V > 0x7FFFFFFF || B * (int64_t(gamma) + 1) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify: sizes must fit 31 bits");
+  if (gamma > 4096) return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify: gamma > 4096");
+  if (tslt::verify_segments(V) + 2 > tslt::kBlock) return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify: V too large");
+  if (B * int64_t(tslt::verify_segments(V)) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify: B too large");
+  if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "tslt_verify: temperature must be > 0");
+  if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify: k_cap must be in 1..%d", TSLT_MAX_K_CAP);
+  if (B == 0) return TSLT_OK;
+  if (!target_logits || !q_idx || !q_logit || !q_count || !draft_tokens || !u_accept || !u_resample ||
+      !out_accept_len || !out_tokens)
+    return fail(TSLT_ERR_INVALID_ARG, "tslt_verify: null pointer");
+  if (reinterpret_cast<uintptr_t>(target_logits) % (dt == TSLT_BF16 ? 2 : 4)) return fail(TSLT_ERR_INVALID_ARG, "tslt_verify: logits not aligned to their element type");
+  const size_t need = tslt::verify_workspace_bytes(B, gamma, V, k_cap);
+  if (!ws || ws_bytes < need || reinterpret_cast<uintptr_t>(ws) % 256)
+    return fail(TSLT_ERR_WORKSPACE, "tslt_verify: workspace of %zu bytes, 256-byte aligned, required", need);
+
+  tslt::VerifyParams p{};
+  p.target = target_logits; p.B = B; p.gamma = gamma; p.V = V; p.row_stride = row_stride;
+  p.rT = reciprocal_temperature(target_temperature);
+  p.k2 = log2e_over_T(p.rT);
+  p.q_idx = q_idx; p.q_logit = q_logit; p.q_count = q_count; p.k_cap = k_cap;
+  p.draft_tokens = draft_tokens; p.u_accept = u_accept; p.u_resample = u_resample;
+  p.out_accept_len = out_accept_len; p.out_tokens = out_tokens; p.out_ratio = out_ratio; p.out_beta = out_beta;
+  p.status = status;
+  tslt::verify_carve_workspace(p, ws);
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  hipError_t e = dt == TSLT_BF16 ? tslt::launch_verify<tslt::Bf16>(p, s) : tslt::launch_verify<float>(p, s);
+  if (e != hipSuccess) return hip_fail(e, "tslt_verify launch");
+  return TSLT_OK;
+}
+
+int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_t V, int64_t row_stride,
+                     float target_temperature, int32_t depth, const int32_t* expansion, const int32_t* q_idx,
+                     const float* q_logit, const int32_t* q_count, int32_t k_cap, const int32_t* cand_tokens,
+                     const float* u_accept, const float* u_resample, int32_t* out_node_token,
+                     int32_t* out_node_slot, int32_t* out_seq, int32_t* out_len, float* out_ratio, int32_t* status,
+                     void* ws, size_t ws_bytes, void* stream) {
+  (void)target_logits; (void)dt; (void)B; (void)V; (void)row_stride; (void)target_temperature; (void)depth;
+  (void)expansion; (void)q_idx; (void)q_logit; (void)q_count; (void)k_cap; (void)cand_tokens; (void)u_accept;
+  (void)u_resample; (void)out_node_token; (void)out_node_slot; (void)out_seq; (void)out_len; (void)out_ratio;
+  (void)status; (void)ws; (void)ws_bytes; (void)stream;
+  return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify_tree: not built yet");
+}
+
+}  // extern "C"

@@ -1,0 +1,227 @@
+"""Thin Python binding over the C-ABI library (include/tslt.h): argument marshalling only.
+
+Every function takes torch tensors that live on the GPU, allocates the outputs and the workspace
+with torch (device memory and streams are torch's job here, nothing else), passes raw device
+pointers and the current HIP stream to the library and returns the output tensors.  There is no
+fallback: if the library is missing, or a tensor is not on a GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtslt.so")
+
+F32, BF16 = 0, 1
+OP_TRUNCATE, OP_SAMPLE, OP_VERIFY, OP_VERIFY_TREE = 0, 1, 2, 3
+ROW_NONFINITE, ROW_EMPTY, ROW_TOKEN_NOT_IN_SET, ROW_EXACT_PATH = 1, 2, 4, 256
+MAX_K_CAP = 1024
+
+EXPORTS = ("tslt_version", "tslt_last_error", "tslt_workspace_bytes", "tslt_truncate", "tslt_sample",
+           "tslt_verify", "tslt_verify_tree")
+
+_lib = None
+
+
+class TsltError(RuntimeError):
+    pass
+
+
+def load(path: Optional[str] = None):
+    """Open the library; raises if it has not been built (python -m paper_2512_16273_amd.build)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise TsltError(f"{path} not found: build it with `python -m paper_2512_16273_amd.build` "
+                        "(there is no CPU fallback)")
+    lib = ctypes.CDLL(path)
+    c = ctypes
+    vp, i32, i64, f32, sz = c.c_void_p, c.c_int32, c.c_int64, c.c_float, c.c_size_t
+    lib.tslt_version.restype = c.c_int
+    lib.tslt_version.argtypes = []
+    lib.tslt_last_error.restype = c.c_char_p
+    lib.tslt_last_error.argtypes = []
+    lib.tslt_workspace_bytes.restype = sz
+    lib.tslt_workspace_bytes.argtypes = [c.c_int, i64, i64, i64, i32]
+    lib.tslt_truncate.restype = c.c_int
+    lib.tslt_truncate.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tslt_sample.restype = c.c_int
+    lib.tslt_sample.argtypes = [vp, vp, vp, i64, i32, vp, i32, i32, vp, vp, vp]
+    lib.tslt_verify.restype = c.c_int
+    lib.tslt_verify.argtypes = [vp, c.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp,
+                                vp, vp, sz, vp]
+    lib.tslt_verify_tree.restype = c.c_int
+    lib.tslt_verify_tree.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, c.POINTER(i32), vp, vp, vp, i32, vp, vp,
+                                     vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _check(code: int):
+    if code != 0:
+        raise TsltError(f"tslt error {code}: {load().tslt_last_error().decode()}")
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TsltError(f"unsupported logits dtype {t.dtype}")
+
+
+def _dev(t: torch.Tensor, dtype=None, name="tensor", contiguous=True) -> torch.Tensor:
+    if not t.is_cuda:
+        raise TsltError(f"{name} must live on the GPU (there is no CPU path)")
+    if dtype is not None and t.dtype != dtype:
+        raise TsltError(f"{name} must be {dtype}, got {t.dtype}")
+    if contiguous and not t.is_contiguous():
+        raise TsltError(f"{name} must be contiguous")
+    return t
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _rows_2d(logits: torch.Tensor):
+    """[..., V] view as rows with a common stride (the last dimension must be dense)."""
+    if logits.stride(-1) != 1:
+        raise TsltError("logits must be dense along the vocabulary")
+    V = logits.shape[-1]
+    if logits.dim() == 1:
+        return 1, V, V
+    flat = logits.reshape(-1, V) if logits.is_contiguous() else logits
+    if flat.dim() != 2:
+        raise TsltError("non-contiguous logits must be 2-D [rows, V]")
+    return flat.shape[0], V, flat.stride(0)
+
+
+def workspace_bytes(op: int, n_outer: int, n_inner: int, V: int, k_cap: int) -> int:
+    return int(load().tslt_workspace_bytes(op, n_outer, n_inner, V, k_cap))
+
+
+def _workspace(nbytes: int, device) -> Optional[torch.Tensor]:
+    if nbytes == 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)   # torch aligns to >= 256 bytes
+
+
+def truncate(logits: torch.Tensor, temperature: float, top_k: int, top_p: float, k_cap: int,
+             want_prob: bool = True, out: Optional[dict] = None) -> dict:
+    """tslt_truncate over logits [..., V].  Returns idx, logit, prob, count, mass, status ([rows, k_cap] /
+    [rows])."""
+    lib = load()
+    _dev(logits, name="logits", contiguous=False)
+    rows, V, stride = _rows_2d(logits)
+    dev = logits.device
+    if out is None:
+        out = {
+            "idx": torch.empty(rows, k_cap, dtype=torch.int32, device=dev),
+            "logit": torch.empty(rows, k_cap, dtype=torch.float32, device=dev),
+            "prob": torch.empty(rows, k_cap, dtype=torch.float32, device=dev) if want_prob else None,
+            "count": torch.empty(rows, dtype=torch.int32, device=dev),
+            "mass": torch.empty(rows, dtype=torch.float32, device=dev),
+            "status": torch.empty(rows, dtype=torch.int32, device=dev),
+        }
+    _check(lib.tslt_truncate(_ptr(logits), _dtype_code(logits), rows, V, stride, float(temperature), int(top_k),
+                             float(top_p), int(k_cap), _ptr(out["idx"]), _ptr(out["logit"]), _ptr(out.get("prob")),
+                             _ptr(out["count"]), _ptr(out.get("mass")), _ptr(out.get("status")), None, 0, _stream()))
+    return out
+
+
+def sample(idx: torch.Tensor, logit: torch.Tensor, count: torch.Tensor, u: torch.Tensor,
+           without_replacement: bool = False, out: Optional[dict] = None) -> dict:
+    """tslt_sample: idx/logit [rows, k_cap], count [rows], u [rows, n] -> token, slot [rows, n]."""
+    lib = load()
+    _dev(idx, torch.int32, "idx"); _dev(logit, torch.float32, "logit"); _dev(count, torch.int32, "count")
+    _dev(u, torch.float32, "u")
+    rows, k_cap = idx.shape
+    u2 = u.reshape(rows, -1)
+    n = u2.shape[1]
+    if out is None:
+        out = {"token": torch.empty(rows, n, dtype=torch.int32, device=idx.device),
+               "slot": torch.empty(rows, n, dtype=torch.int32, device=idx.device)}
+    _check(lib.tslt_sample(_ptr(idx), _ptr(logit), _ptr(count), rows, k_cap, _ptr(u2), n,
+                           1 if without_replacement else 0, _ptr(out["token"]), _ptr(out.get("slot")), _stream()))
+    return out
+
+
+def verify(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logit: torch.Tensor,
+           q_count: torch.Tensor, draft_tokens: torch.Tensor, u_accept: torch.Tensor, u_resample: torch.Tensor,
+           out: Optional[dict] = None, workspace: Optional[torch.Tensor] = None) -> dict:
+    """tslt_verify: target [B, gamma+1, V]; sparse sets [B, gamma, k_cap]; returns accept_len [B],
+    tokens [B, gamma+1], ratio, beta [B, gamma], status [B]."""
+    lib = load()
+    _dev(target, name="target")
+    if target.dim() != 3:
+        raise TsltError("target must be [B, gamma+1, V]")
+    B, g1, V = target.shape
+    gamma = g1 - 1
+    _dev(q_idx, torch.int32, "q_idx"); _dev(q_logit, torch.float32, "q_logit"); _dev(q_count, torch.int32, "q_count")
+    _dev(draft_tokens, torch.int32, "draft_tokens"); _dev(u_accept, torch.float32, "u_accept")
+    _dev(u_resample, torch.float32, "u_resample")
+    k_cap = q_idx.shape[-1]
+    if q_idx.numel() != B * gamma * k_cap or u_resample.numel() != B * g1 or u_accept.numel() != B * gamma:
+        raise TsltError("verify: shapes do not agree")
+    dev = target.device
+    if out is None:
+        out = {"accept_len": torch.empty(B, dtype=torch.int32, device=dev),
+               "tokens": torch.empty(B, g1, dtype=torch.int32, device=dev),
+               "ratio": torch.empty(B, gamma, dtype=torch.float32, device=dev),
+               "beta": torch.empty(B, gamma, dtype=torch.float32, device=dev),
+               "status": torch.empty(B, dtype=torch.int32, device=dev)}
+    need = workspace_bytes(OP_VERIFY, B, gamma, V, k_cap)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    _check(lib.tslt_verify(_ptr(target), _dtype_code(target), B, gamma, V, target.stride(1), float(temperature),
+                           _ptr(q_idx), _ptr(q_logit), _ptr(q_count), k_cap, _ptr(draft_tokens), _ptr(u_accept),
+                           _ptr(u_resample), _ptr(out["accept_len"]), _ptr(out["tokens"]), _ptr(out.get("ratio")),
+                           _ptr(out.get("beta")), _ptr(out.get("status")), _ptr(ws), ws.numel() if ws is not None else 0,
+                           _stream()))
+    return out
+
+
+def verify_tree(target: torch.Tensor, temperature: float, expansion: Sequence[int], q_idx: torch.Tensor,
+                q_logit: torch.Tensor, q_count: torch.Tensor, cand_tokens: torch.Tensor, u_accept: torch.Tensor,
+                u_resample: torch.Tensor, all_nodes: bool = True, out: Optional[dict] = None,
+                workspace: Optional[torch.Tensor] = None) -> dict:
+    """tslt_verify_tree: target [B, N_nodes, V]; sparse sets [B, N_int, k_cap]; cand_tokens, u_accept
+    [B, N_nodes-1]; u_resample [B, N_nodes].  Returns seq [B, depth+1], len [B], node_token / node_slot
+    [B, N_nodes] (when all_nodes), ratio [B, N_nodes-1], status [B]."""
+    lib = load()
+    _dev(target, name="target")
+    if target.dim() != 3:
+        raise TsltError("target must be [B, N_nodes, V]")
+    B, n_nodes, V = target.shape
+    depth = len(expansion)
+    _dev(q_idx, torch.int32, "q_idx"); _dev(q_logit, torch.float32, "q_logit"); _dev(q_count, torch.int32, "q_count")
+    _dev(cand_tokens, torch.int32, "cand_tokens"); _dev(u_accept, torch.float32, "u_accept")
+    _dev(u_resample, torch.float32, "u_resample")
+    k_cap = q_idx.shape[-1]
+    dev = target.device
+    if out is None:
+        out = {"seq": torch.empty(B, depth + 1, dtype=torch.int32, device=dev),
+               "len": torch.empty(B, dtype=torch.int32, device=dev),
+               "node_token": torch.empty(B, n_nodes, dtype=torch.int32, device=dev) if all_nodes else None,
+               "node_slot": torch.empty(B, n_nodes, dtype=torch.int32, device=dev) if all_nodes else None,
+               "ratio": torch.empty(B, max(n_nodes - 1, 1), dtype=torch.float32, device=dev),
+               "status": torch.empty(B, dtype=torch.int32, device=dev)}
+    need = workspace_bytes(OP_VERIFY_TREE, B, n_nodes, V, k_cap)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    exp_arr = (ctypes.c_int32 * depth)(*[int(k) for k in expansion])
+    _check(lib.tslt_verify_tree(_ptr(target), _dtype_code(target), B, V, target.stride(1), float(temperature), depth,
+                                exp_arr, _ptr(q_idx), _ptr(q_logit), _ptr(q_count), k_cap, _ptr(cand_tokens),
+                                _ptr(u_accept), _ptr(u_resample), _ptr(out.get("node_token")),
+                                _ptr(out.get("node_slot")), _ptr(out["seq"]), _ptr(out["len"]), _ptr(out.get("ratio")),
+                                _ptr(out.get("status")), _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
+    return out

@@ -1,0 +1,138 @@
+"""GPU parity: tslt_verify through the C ABI against the CPU oracle, and the whole single-candidate
+round truncate -> sample -> verify."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tslt_oracle as O
+from paper_2512_16273_amd import workloads as W
+from tests import _parity as P
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def t32(a, dtype=None):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV) if dtype is None else \
+        torch.from_numpy(np.ascontiguousarray(a)).to(dtype).to(DEV)
+
+
+def run_verify_from_oracle_inputs(tslt, w, chain, ref):
+    return tslt.verify(chain["target"], w.T, t32(ref["q_idx"]), t32(ref["q_logit"]), t32(ref["q_count"]),
+                       t32(ref["tokens"]), chain["u_accept"], chain["u_resample"])
+
+
+@pytest.mark.parametrize("name,base,kw", [
+    ("tiny", "tiny", {}),
+    ("f32-odd", "tiny", dict(B=6, V=5003, gamma=3)),
+    ("bf16-topk", "chain_topk", dict(B=12, V=20011)),
+    ("bf16-topp", "chain_topp", dict(B=10)),
+    ("bf16-k1024", "stress", dict(B=3, gamma=4, V=70000)),
+    ("bf16-one-segment", "chain_topk", dict(B=5, V=2000, gamma=2)),
+])
+def test_verify_matches_oracle(tslt, name, base, kw):
+    w = W.scaled(W.WORKLOADS[base], **kw)
+    chain = W.make_chain(w, 7, DEV)
+    ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), w.T, w.top_k, w.top_p, w.k_cap,
+                         P.to_np(chain["u_sample"]), P.to_np(chain["u_accept"]), P.to_np(chain["u_resample"]))
+    out = run_verify_from_oracle_inputs(tslt, w, chain, ref)
+    torch.cuda.synchronize()
+    res = P.compare_verify(out, ref["verify"], label=name)
+    print(name, res, "accept_len histogram", np.bincount(ref["verify"]["accept_len"], minlength=w.gamma + 1))
+
+
+def test_round_truncate_sample_verify(tslt):
+    """The three calls chained on the GPU reproduce the oracle's round."""
+    w = W.scaled(W.WORKLOADS["chain_topp"], B=16)
+    chain = W.make_chain(w, 21, DEV)
+    B, G, V = w.B, w.gamma, w.V
+    tr = tslt.truncate(chain["draft"], w.T, w.top_k, w.top_p, w.k_cap)
+    smp = tslt.sample(tr["idx"], tr["logit"], tr["count"], chain["u_sample"].reshape(B * G, 1))
+    out = tslt.verify(chain["target"], w.T, tr["idx"].view(B, G, -1), tr["logit"].view(B, G, -1),
+                      tr["count"].view(B, G), smp["token"].view(B, G), chain["u_accept"], chain["u_resample"])
+    torch.cuda.synchronize()
+    ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), w.T, w.top_k, w.top_p, w.k_cap,
+                         P.to_np(chain["u_sample"]), P.to_np(chain["u_accept"]), P.to_np(chain["u_resample"]))
+    t = P.compare_truncate(tr, chain["draft"].reshape(B * G, V), w.T, w.top_k, w.top_p, w.k_cap, label="round")
+    if t["top_p_near_ties"] == 0:
+        assert np.array_equal(P.to_np(smp["token"]).reshape(B, G), ref["tokens"])
+        print(P.compare_verify(out, ref["verify"], label="round"))
+
+
+def test_verify_forced_paths_and_broken_rows(tslt):
+    """All-accepted (bonus row), immediate rejection, tokens outside their set, NaN / masked rows."""
+    w = W.scaled(W.WORKLOADS["chain_topk"], B=8, V=9001, gamma=4)
+    chain = W.make_chain(w, 3, DEV)
+    target = chain["target"].clone()
+    target[4, 1, 17] = float("nan")          # broken row in the middle of sequence 4
+    target[5, w.gamma, 5] = float("inf")     # broken bonus row of sequence 5
+    target[6, 0, :] = -float("inf")          # fully masked row
+    target[7, 2, 100:] = -float("inf")       # mostly masked row
+    chain["target"] = target
+    u_acc = chain["u_accept"].clone()
+    u_acc[0] = 0.0                            # sequence 0: everything accepted -> bonus token
+    u_acc[1] = 0.99999994                     # sequence 1: rejected wherever ratio < 1
+    u_acc[5] = 0.0
+    chain["u_accept"] = u_acc
+    ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(target), w.T, w.top_k, w.top_p, w.k_cap,
+                         P.to_np(chain["u_sample"]), P.to_np(u_acc), P.to_np(chain["u_resample"]))
+    # sequence 2: draft tokens that are not in their sets
+    toks = ref["tokens"].copy()
+    outside = np.setdiff1d(np.arange(w.V), ref["q_idx"][2, 0])[:w.gamma]
+    toks[2] = outside
+    ref["tokens"] = toks
+    ref["verify"] = O.verify_chain(P.to_np(target), w.T, ref["q_idx"], ref["q_logit"], ref["q_count"], toks,
+                                   P.to_np(u_acc), P.to_np(chain["u_resample"]))
+    out = run_verify_from_oracle_inputs(tslt, w, chain, ref)
+    torch.cuda.synchronize()
+    v = ref["verify"]
+    assert v["accept_len"][0] == w.gamma and v["status"][2] & 4 and v["status"][4] & 1 and v["status"][5] & 1
+    print(P.compare_verify(out, v, label="forced"), v["accept_len"], v["status"])
+
+
+def test_verify_argument_errors(tslt):
+    w = W.scaled(W.WORKLOADS["chain_topk"], B=2, V=3000, gamma=2)
+    chain = W.make_chain(w, 3, DEV)
+    ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), w.T, w.top_k, w.top_p, w.k_cap,
+                         P.to_np(chain["u_sample"]), P.to_np(chain["u_accept"]), P.to_np(chain["u_resample"]))
+    args = [chain["target"], w.T, t32(ref["q_idx"]), t32(ref["q_logit"]), t32(ref["q_count"]), t32(ref["tokens"]),
+            chain["u_accept"], chain["u_resample"]]
+    with pytest.raises(tslt.TsltError):
+        tslt.verify(*args, workspace=torch.empty(16, dtype=torch.uint8, device=DEV))   # workspace too small
+    bad = list(args)
+    bad[1] = 0.0
+    with pytest.raises(tslt.TsltError):
+        tslt.verify(*bad)
+
+
+def test_large_vocab_full_size_sampled_sequences(tslt):
+    """BASELINE config 3 at full size (B=256, gamma=8, V=128256, bf16), the configuration bench.py
+    times: the GPU runs the whole batch; sampled sequences are checked against the oracle, which is fed
+    its own truncation of those sequences' draft rows."""
+    w = W.WORKLOADS["large_vocab"]
+    chain = W.make_chain(w, 0, DEV)
+    B, G, V = w.B, w.gamma, w.V
+    tr = tslt.truncate(chain["draft"], w.T, w.top_k, w.top_p, w.k_cap)
+    smp = tslt.sample(tr["idx"], tr["logit"], tr["count"], chain["u_sample"].reshape(B * G, 1))
+    q_idx, q_logit = tr["idx"].view(B, G, -1).clone(), tr["logit"].view(B, G, -1).clone()
+    q_count, toks = tr["count"].view(B, G).clone(), smp["token"].view(B, G).clone()
+    seqs = np.random.default_rng(1).choice(B, 6, replace=False)
+    sel = torch.from_numpy(seqs).to(DEV)
+    ref = P.oracle_chain(P.to_np(chain["draft"][sel]), P.to_np(chain["target"][sel]), w.T, w.top_k, w.top_p, w.k_cap,
+                         P.to_np(chain["u_sample"][sel]), P.to_np(chain["u_accept"][sel]),
+                         P.to_np(chain["u_resample"][sel]))
+    # the sampled sequences get the oracle's own sparse sets and tokens as inputs
+    q_idx[sel], q_logit[sel] = t32(ref["q_idx"]), t32(ref["q_logit"])
+    q_count[sel], toks[sel] = t32(ref["q_count"]), t32(ref["tokens"])
+    out = tslt.verify(chain["target"], w.T, q_idx, q_logit, q_count, toks, chain["u_accept"], chain["u_resample"])
+    torch.cuda.synchronize()
+    print(P.compare_verify(out, ref["verify"], seqs=seqs, label="large_vocab"))
+    # properties over the whole batch
+    n = out["accept_len"].long()
+    assert int(n.min()) >= 0 and int(n.max()) <= G
+    tk = out["tokens"].long()
+    pos = torch.arange(G + 1, device=DEV)[None, :]
+    assert torch.all((tk >= 0) == (pos <= n[:, None]))
+    assert torch.all(tk[:, :G][pos[:, :G] < n[:, None]] == toks.long()[pos[:, :G] < n[:, None]])
+    assert torch.all(out["status"] == 0)
+    print("mean accepted length", float(n.float().mean()))
