@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the TSLT hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic logits already resident in
+HBM: tslt_truncate on every draft row, tslt_sample of the draft token, tslt_verify (acceptance tests
+on every target row, then residual / bonus resampling).  Workload: BASELINE config "large_vocab"
+(B=256, gamma=8, V=128256, bf16, T=0.7, top-p 0.9 with K cap 256).  Three independent input sets
+(3.4 GB) are rotated so that the 256 MB Infinity Cache cannot serve repeats.
+
+Prints ONE JSON line: positions/s (B*gamma per step), the roofline of the dominant kernel measured with
+events on the launch stream inside the timed region, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(w):
+    """Bytes the method has to move per step ("algorithmic bytes")."""
+    s = 2 if w.dtype == "bf16" else 4
+    rows_d, rows_t = w.B * w.gamma, w.B * (w.gamma + 1)
+    draft = rows_d * w.V * s
+    sparse_w = rows_d * w.k_cap * (4 + 4 + 4)          # idx, logit, prob written by truncate
+    sparse_r = rows_d * w.k_cap * (4 + 4)              # idx, logit read by verify
+    target = rows_t * w.V * s
+    return {"truncate": draft + sparse_w, "verify_accept": (rows_t - w.B) * w.V * s + sparse_r,
+            "verify_resample": w.B * w.V * s, "total": draft + target + sparse_w + sparse_r}
+
+
+def committed_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", "large_vocab_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(rf"^traffic_bytes_per_launch\s+{kernel}\s+([0-9.eE+]+)", open(path).read(), re.M)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(w, seed):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+    import numpy as np
+    import torch
+    from oracle import tslt_oracle as O
+    from paper_2512_16273_amd import workloads as W
+    n_seq = 3
+    ws = W.scaled(w, B=n_seq)
+    c = W.make_chain(ws, seed, "cpu")
+    draft = c["draft"].float().numpy().reshape(n_seq * w.gamma, w.V)
+    target = c["target"].float().numpy()
+    t0 = time.perf_counter()
+    done = 0
+    for b in range(n_seq):
+        rows = draft[b * w.gamma:(b + 1) * w.gamma]
+        tr = O.truncate(rows, w.T, w.top_k, w.top_p, w.k_cap)
+        smp = O.sample(tr["idx"], tr["logit"], tr["count"], c["u_sample"][b].numpy().reshape(w.gamma, 1))
+        O.verify_chain_seq(target[b], w.T, tr["idx"], tr["logit"], tr["count"], smp["token"][:, 0],
+                           c["u_accept"][b].numpy(), c["u_resample"][b].numpy())
+        done += 1
+        if time.perf_counter() - t0 > 25.0:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": done * w.gamma / dt, "unit": "draft positions/s", "cores": 1, "kind": "oracle",
+            "sample": f"{done} sequences x gamma={w.gamma} of the same workload (truncate+sample+verify, "
+                      f"NumPy fp64, single thread), {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--workload", default="large_vocab")
+    ap.add_argument("--sets", type=int, default=3, help="independent input sets rotated between steps")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-events", action="store_true", help="time the steps without per-kernel events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (sequences would shard across GPUs with no exchange; "
+              "see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_16273_amd import tslt, workloads as W
+    tslt.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    w = W.WORKLOADS[args.workload]
+    B, G, V, K = w.B, w.gamma, w.V, w.k_cap
+
+    sets = []
+    for i in range(args.sets):
+        c = W.make_chain(w, 100 + i, dev)
+        sets.append(c)
+    # preallocated outputs and workspace: nothing is allocated inside the timed region
+    tr_out = {"idx": torch.empty(B * G, K, dtype=torch.int32, device=dev),
+              "logit": torch.empty(B * G, K, dtype=torch.float32, device=dev),
+              "prob": torch.empty(B * G, K, dtype=torch.float32, device=dev),
+              "count": torch.empty(B * G, dtype=torch.int32, device=dev),
+              "mass": torch.empty(B * G, dtype=torch.float32, device=dev),
+              "status": torch.empty(B * G, dtype=torch.int32, device=dev)}
+    sm_out = {"token": torch.empty(B * G, 1, dtype=torch.int32, device=dev),
+              "slot": torch.empty(B * G, 1, dtype=torch.int32, device=dev)}
+    vf_out = {"accept_len": torch.empty(B, dtype=torch.int32, device=dev),
+              "tokens": torch.empty(B, G + 1, dtype=torch.int32, device=dev),
+              "ratio": torch.empty(B, G, dtype=torch.float32, device=dev),
+              "beta": torch.empty(B, G, dtype=torch.float32, device=dev),
+              "status": torch.empty(B, dtype=torch.int32, device=dev)}
+    ws = torch.empty(tslt.workspace_bytes(tslt.OP_VERIFY, B, G, V, K), dtype=torch.uint8, device=dev)
+    q_idx, q_logit = tr_out["idx"].view(B, G, K), tr_out["logit"].view(B, G, K)
+    q_count, toks = tr_out["count"].view(B, G), sm_out["token"].view(B, G)
+
+    def step(c, ev=None):
+        if ev: ev[0].record()
+        tslt.truncate(c["draft"], w.T, w.top_k, w.top_p, K, out=tr_out)
+        if ev: ev[1].record()
+        tslt.sample(tr_out["idx"], tr_out["logit"], tr_out["count"], c["u_sample"].view(B * G, 1), out=sm_out)
+        if ev: ev[2].record()
+        tslt.verify(c["target"], w.T, q_idx, q_logit, q_count, toks, c["u_accept"], c["u_resample"], out=vf_out,
+                    workspace=ws, phase="accept")
+        if ev: ev[3].record()
+        tslt.verify(c["target"], w.T, q_idx, q_logit, q_count, toks, c["u_accept"], c["u_resample"], out=vf_out,
+                    workspace=ws, phase="resample")
+        if ev: ev[4].record()
+
+    for i in range(args.warmup):
+        step(sets[i % len(sets)])
+    torch.cuda.synchronize()
+    events = None
+    if not args.no_events:
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(sets[i % len(sets)], events[i] if events else None)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = dt / args.steps * 1e3
+    alg = algorithmic_bytes(w)
+    kernels = {}
+    roofline = None
+    if events:
+        names = ["truncate", "sample", "verify_accept", "verify_resample"]
+        for k, name in enumerate(names):
+            ts = [events[i][k].elapsed_time(events[i][k + 1]) for i in range(args.steps)]
+            kernels[name] = {"avg_ms": sum(ts) / len(ts), "min_ms": min(ts)}
+        dom = max(("truncate", "verify_accept"), key=lambda n: kernels[n]["avg_ms"])
+        kname = {"truncate": "truncate_kernel", "verify_accept": "verify_accept_kernel"}[dom]
+        achieved = alg[dom] / (kernels[dom]["avg_ms"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "algorithmic_bytes_per_launch": alg[dom], "avg_launch_ms": round(kernels[dom]["avg_ms"], 4),
+                    "traffic": committed_traffic(kname)}
+        for n in ("truncate", "verify_accept", "verify_resample"):
+            kernels[n]["GBps"] = round(alg[n] / (kernels[n]["avg_ms"] * 1e-3) / 1e9, 1)
+            kernels[n]["avg_ms"] = round(kernels[n]["avg_ms"], 4)
+            kernels[n]["min_ms"] = round(kernels[n]["min_ms"], 4)
+        kernels["sample"] = {k: round(v, 4) for k, v in kernels["sample"].items()}
+
+    res = {
+        "metric": "draft positions truncated+verified/sec at V=128k; achieved HBM GB/s vs peak",
+        "value": round(B * G * args.steps / dt, 1), "unit": "draft positions/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={B} gamma={G} V={V} {w.dtype} logits, T={w.T}, top_p={w.top_p}, "
+                               f"k_cap={K}; {args.sets} rotating input sets; truncate+sample+verify per step",
+                   "storage_dtype": w.dtype},
+        "hbm_GBps_whole_step": round(alg["total"] / (dt / args.steps) / 1e9, 1),
+        "hbm_frac_whole_step": round(alg["total"] / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+        "kernels": kernels, "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, 100)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

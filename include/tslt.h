@@ -142,6 +142,25 @@ int tslt_verify(const void* target_logits, tslt_dtype dt, int64_t B, int32_t gam
                 int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta,
                 int32_t* status, void* ws, size_t ws_bytes, void* stream);
 
+/* The two halves of tslt_verify as separate calls, for callers that want to put work (or timing
+ * events) between them; same arguments, same workspace.  tslt_verify_accept evaluates the acceptance
+ * tests of Algorithm 3 for every position (writes out_ratio, out_beta and the decisions, into the
+ * workspace); tslt_verify_resample then finds the first rejection, draws the replacement or bonus
+ * token and writes out_accept_len, out_tokens and status.  tslt_verify == accept followed by resample
+ * on the same stream with the same workspace. */
+int tslt_verify_accept(const void* target_logits, tslt_dtype dt, int64_t B, int32_t gamma, int64_t V,
+                       int64_t row_stride, float target_temperature,
+                       const int32_t* q_idx, const float* q_logit, const int32_t* q_count, int32_t k_cap,
+                       const int32_t* draft_tokens, const float* u_accept, const float* u_resample,
+                       int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta,
+                       int32_t* status, void* ws, size_t ws_bytes, void* stream);
+int tslt_verify_resample(const void* target_logits, tslt_dtype dt, int64_t B, int32_t gamma, int64_t V,
+                         int64_t row_stride, float target_temperature,
+                         const int32_t* q_idx, const float* q_logit, const int32_t* q_count, int32_t k_cap,
+                         const int32_t* draft_tokens, const float* u_accept, const float* u_resample,
+                         int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta,
+                         int32_t* status, void* ws, size_t ws_bytes, void* stream);
+
 /* Token-tree verification (Algorithm 8 with Algorithm 5 at every non-leaf node) for B trees.
  *
  * Nodes are stored breadth-first (Section 4.1): layer l has W_l = k_1*...*k_l nodes, the i-th node of

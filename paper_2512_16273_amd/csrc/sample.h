@@ -2,6 +2,7 @@
 // Algorithm 4 for several candidates), one wave per row, fp64 throughout.
 #pragma once
 #include "common.h"
+#include "exp64.h"
 
 namespace tslt {
 
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(64) void sample_kernel(const SampleParams p) {
 #pragma unroll
   for (int r = 0; r < kSamplePer; ++r) {
     const int i = lane * per + r;
-    w[r] = (r < per && i < count) ? exp(double(lg[i]) - s0) : 0.0;
+    w[r] = (r < per && i < count) ? exp64(double(lg[i]) - s0) : 0.0;
   }
   for (int c = 0; c < p.n_samples; ++c) {
     double local = 0.0;

@@ -12,6 +12,7 @@
 // fp64, which is also where Top-rho and the renormalisation are decided.
 #pragma once
 #include "common.h"
+#include "exp64.h"
 
 namespace tslt {
 
@@ -364,7 +365,7 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
       const float v = cand_value(c);
       idx[r] = cand_index(c);
       s32[r] = __fmul_rn(v, p.rT);
-      e64[r] = exp(double(s32[r]) - double(m_s));
+      e64[r] = exp64(double(s32[r]) - double(m_s));
       local += e64[r];
       head32 += double(fast_exp2(__builtin_fmaf(v, p.k2, -c_ref)));
     }

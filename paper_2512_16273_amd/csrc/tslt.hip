@@ -157,27 +157,27 @@ int tslt_sample(const int32_t* idx, const float* logit, const int32_t* count, in
   return TSLT_OK;
 }
 
-int tslt_verify(const void* target_logits, tslt_dtype dt, int64_t B, int32_t gamma, int64_t V, int64_t row_stride,
-                float target_temperature, const int32_t* q_idx, const float* q_logit, const int32_t* q_count,
-                int32_t k_cap, const int32_t* draft_tokens, const float* u_accept, const float* u_resample,
-                int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta, int32_t* status,
-                void* ws, size_t ws_bytes, void* stream) {
-  if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "tslt_verify: unknown dtype %d", int(dt));
-  if (B < 0 || gamma < 1 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "tslt_verify: bad shape");
-  if (V > 0x7FFFFFFF || B * (int64_t(gamma) + 1) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify: sizes must fit 31 bits");
-  if (gamma > 4096) return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify: gamma > 4096");
-  if (tslt::verify_segments(V) + 2 > tslt::kBlock) return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify: V too large");
-  if (B * int64_t(tslt::verify_segments(V)) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify: B too large");
-  if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "tslt_verify: temperature must be > 0");
-  if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify: k_cap must be in 1..%d", TSLT_MAX_K_CAP);
+static int verify_impl(int phases, const char* name, const void* target_logits, tslt_dtype dt, int64_t B,
+                       int32_t gamma, int64_t V, int64_t row_stride, float target_temperature, const int32_t* q_idx,
+                       const float* q_logit, const int32_t* q_count, int32_t k_cap, const int32_t* draft_tokens,
+                       const float* u_accept, const float* u_resample, int32_t* out_accept_len, int32_t* out_tokens,
+                       float* out_ratio, float* out_beta, int32_t* status, void* ws, size_t ws_bytes, void* stream) {
+  if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "%s: unknown dtype %d", name, int(dt));
+  if (B < 0 || gamma < 1 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "%s: bad shape", name);
+  if (V > 0x7FFFFFFF || B * (int64_t(gamma) + 1) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: sizes must fit 31 bits", name);
+  if (gamma > 4096) return fail(TSLT_ERR_UNSUPPORTED, "%s: gamma > 4096", name);
+  if (tslt::verify_segments(V) + 2 > tslt::kBlock) return fail(TSLT_ERR_UNSUPPORTED, "%s: V too large", name);
+  if (B * int64_t(tslt::verify_segments(V)) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: B too large", name);
+  if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "%s: temperature must be > 0", name);
+  if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "%s: k_cap must be in 1..%d", name, TSLT_MAX_K_CAP);
   if (B == 0) return TSLT_OK;
   if (!target_logits || !q_idx || !q_logit || !q_count || !draft_tokens || !u_accept || !u_resample ||
       !out_accept_len || !out_tokens)
-    return fail(TSLT_ERR_INVALID_ARG, "tslt_verify: null pointer");
-  if (reinterpret_cast<uintptr_t>(target_logits) % (dt == TSLT_BF16 ? 2 : 4)) return fail(TSLT_ERR_INVALID_ARG, "tslt_verify: logits not aligned to their element type");
+    return fail(TSLT_ERR_INVALID_ARG, "%s: null pointer", name);
+  if (reinterpret_cast<uintptr_t>(target_logits) % (dt == TSLT_BF16 ? 2 : 4)) return fail(TSLT_ERR_INVALID_ARG, "%s: logits not aligned to their element type", name);
   const size_t need = tslt::verify_workspace_bytes(B, gamma, V, k_cap);
   if (!ws || ws_bytes < need || reinterpret_cast<uintptr_t>(ws) % 256)
-    return fail(TSLT_ERR_WORKSPACE, "tslt_verify: workspace of %zu bytes, 256-byte aligned, required", need);
+    return fail(TSLT_ERR_WORKSPACE, "%s: workspace of %zu bytes, 256-byte aligned, required", name, need);
 
   tslt::VerifyParams p{};
   p.target = target_logits; p.B = B; p.gamma = gamma; p.V = V; p.row_stride = row_stride;
@@ -189,10 +189,23 @@ int tslt_verify(const void* target_logits, tslt_dtype dt, int64_t B, int32_t gam
   p.status = status;
   tslt::verify_carve_workspace(p, ws);
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  hipError_t e = dt == TSLT_BF16 ? tslt::launch_verify<tslt::Bf16>(p, s) : tslt::launch_verify<float>(p, s);
-  if (e != hipSuccess) return hip_fail(e, "tslt_verify launch");
+  hipError_t e = dt == TSLT_BF16 ? tslt::launch_verify<tslt::Bf16>(p, s, phases) : tslt::launch_verify<float>(p, s, phases);
+  if (e != hipSuccess) return hip_fail(e, name);
   return TSLT_OK;
 }
+
+#define TSLT_VERIFY_ARGS                                                                                          \
+  const void *target_logits, tslt_dtype dt, int64_t B, int32_t gamma, int64_t V, int64_t row_stride,             \
+      float target_temperature, const int32_t *q_idx, const float *q_logit, const int32_t *q_count, int32_t k_cap, \
+      const int32_t *draft_tokens, const float *u_accept, const float *u_resample, int32_t *out_accept_len,       \
+      int32_t *out_tokens, float *out_ratio, float *out_beta, int32_t *status, void *ws, size_t ws_bytes, void *stream
+#define TSLT_VERIFY_PASS                                                                                           \
+  target_logits, dt, B, gamma, V, row_stride, target_temperature, q_idx, q_logit, q_count, k_cap, draft_tokens,   \
+      u_accept, u_resample, out_accept_len, out_tokens, out_ratio, out_beta, status, ws, ws_bytes, stream
+
+int tslt_verify(TSLT_VERIFY_ARGS) { return verify_impl(3, "tslt_verify", TSLT_VERIFY_PASS); }
+int tslt_verify_accept(TSLT_VERIFY_ARGS) { return verify_impl(1, "tslt_verify_accept", TSLT_VERIFY_PASS); }
+int tslt_verify_resample(TSLT_VERIFY_ARGS) { return verify_impl(2, "tslt_verify_resample", TSLT_VERIFY_PASS); }
 
 int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_t V, int64_t row_stride,
                      float target_temperature, int32_t depth, const int32_t* expansion, const int32_t* q_idx,

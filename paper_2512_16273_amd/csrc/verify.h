@@ -6,15 +6,18 @@
 // p at those indices, q_hat = softmax of the received values, the ratio p(x)/q_hat(x) of the draft
 // token, the acceptance decision u < min(1, ratio) and Lemma 1's sum min(p, q_hat).
 //
-// Kernel B, a few workgroups per sequence: finds the first rejected position j (or the bonus row)
-// from kernel A's decisions and sweeps that one target row in fp64, each workgroup a segment; the
-// last workgroup to finish a sequence combines the segment sums, applies the sparse corrections
+// Kernel B1, a few workgroups per sequence: finds the first rejected position j (or the bonus row)
+// from kernel A's decisions and sweeps that one target row in fp64, each workgroup a segment.
+// Kernel B2, one workgroup per sequence: combines the segment sums, applies the sparse corrections
 // max(0, p - q_hat) - p at the draft set's indices, locates the segment, the 64-element chunk and
 // finally the element at which the cumulative residual mass passes u * total, and writes the
-// sequence's outputs.  fp64 is needed here: at V >= 128k the buckets of the inverse CDF are far
+// sequence's outputs.  (Two kernels rather than a "last workgroup finishes" scheme: a device-scope
+// fence per workgroup writes back and invalidates the L2 of the XCD, which costs far more than a
+// launch.)  fp64 is needed here: at V >= 128k the buckets of the inverse CDF are far
 // narrower than fp32 prefix sums can resolve.
 #pragma once
 #include "common.h"
+#include "exp64.h"
 
 namespace tslt {
 
@@ -22,7 +25,7 @@ constexpr int kSegVecs = 8;                         // 16-byte vectors per threa
 constexpr int kSegVecsTotal = kSegVecs * kBlock;    // vectors per segment
 
 struct SegResult {       // one segment (or edge piece) of the resampled row
-  double sum;            // sum of exp(s - smax) over the piece
+  double sum;            // sum of exp64(s - smax) over the piece
   float smax;            // largest scaled logit of the piece (-inf if empty)
   int bad;               // NaN or +inf seen
 };
@@ -47,10 +50,9 @@ struct VerifyParams {
   // workspace
   int32_t* flags;        // [B, gamma] 1 accepted, 0 rejected, 2 row unusable
   int32_t* row_status;   // [B, gamma]
-  uint32_t* counters;    // [B] workgroups of kernel B that have finished the sequence
   SegResult* segs;       // [B, n_pieces]
   int n_seg;             // body segments per row (upper bound used for the layout)
-  int n_seg_grid;        // workgroups of kernel B per sequence
+  int n_seg_grid;        // workgroups of kernel B1 per sequence
 };
 
 inline int verify_segments(int64_t V) {
@@ -62,13 +64,12 @@ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 inline size_t verify_workspace_bytes(int64_t B, int64_t gamma, int64_t V, int k_cap) {
   (void)k_cap;
   const size_t n_pieces = size_t(verify_segments(V)) + 2;
-  return align256(size_t(B) * gamma * 4) * 2 + align256(size_t(B) * 4) + align256(size_t(B) * n_pieces * sizeof(SegResult));
+  return align256(size_t(B) * gamma * 4) * 2 + align256(size_t(B) * n_pieces * sizeof(SegResult));
 }
 inline void verify_carve_workspace(VerifyParams& p, void* ws) {
   char* w = reinterpret_cast<char*>(ws);
   p.flags = reinterpret_cast<int32_t*>(w); w += align256(size_t(p.B) * p.gamma * 4);
   p.row_status = reinterpret_cast<int32_t*>(w); w += align256(size_t(p.B) * p.gamma * 4);
-  p.counters = reinterpret_cast<uint32_t*>(w); w += align256(size_t(p.B) * 4);
   p.segs = reinterpret_cast<SegResult*>(w);
   p.n_seg = verify_segments(p.V);
 }
@@ -102,7 +103,6 @@ __global__ __launch_bounds__(kBlock) void verify_accept_kernel(const VerifyParam
   const RowSplit rs = split_row<T>(row, p.V);
   const int n_edge = rs.head + rs.tail;
   const int64_t n_tiles = (rs.nvec + kBlock - 1) / kBlock;
-  if (j == 0 && tid == 0) p.counters[b] = 0;
 
   // ---- the received sparse set: gather the target logits at its indices -----------------------
   int count = p.q_count[r];
@@ -196,10 +196,10 @@ __global__ __launch_bounds__(kBlock) void verify_accept_kernel(const VerifyParam
     const int i = tid + k * kBlock;
     e64[k] = 0.0; w64[k] = 0.0;
     if (i < count) {
-      w64[k] = exp(double(ql[i]) - ql0);
+      w64[k] = exp64(double(ql[i]) - ql0);
       sum_w += w64[k];
       if (yi[k] >= 0 && tv[k] > -INFINITY && ok) {
-        e64[k] = exp(double(__fmul_rn(tv[k], p.rT)) - double(s_ref));
+        e64[k] = exp64(double(__fmul_rn(tv[k], p.rT)) - double(s_ref));
         sum_e += e64[k];
         sum_t32 += double(fast_exp2(__builtin_fmaf(tv[k], p.k2, -c_ref)));
       }
@@ -287,7 +287,7 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
     // unnormalised target mass of every piece, referenced to the row maximum, and their total z_p
     double zp = 0.0;
     for (int k = tid; k < n_pieces; k += kBlock) {
-      const double t = segs[k].smax > -INFINITY ? segs[k].sum * exp(double(segs[k].smax) - double(smax)) : 0.0;
+      const double t = segs[k].smax > -INFINITY ? segs[k].sum * exp64(double(segs[k].smax) - double(smax)) : 0.0;
       sh.thread_corr[k] = t;              // n_pieces <= kBlock (checked on the host)
       zp += t;
     }
@@ -309,7 +309,7 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
     for (int k = 0; k < kMaxPer; ++k) {
       const int i = tid + k * kBlock;
       w64[k] = 0.0; corr[k] = 0.0; yi[k] = -1;
-      if (i < count) { w64[k] = exp(double(ql[i]) - ql0); sum_w += w64[k]; }
+      if (i < count) { w64[k] = exp64(double(ql[i]) - ql0); sum_w += w64[k]; }
     }
     sum_w = block_sum_f64<kWaves>(sum_w, sh.red);
     double sum_corr = 0.0;
@@ -321,7 +321,7 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
         if (y >= 0 && y < p.V) {
           yi[k] = y;
           const float t = load_elem<T>(row, y);
-          const double e = t > -INFINITY ? exp(double(__fmul_rn(t, p.rT)) - double(smax)) : 0.0;
+          const double e = t > -INFINITY ? exp64(double(__fmul_rn(t, p.rT)) - double(smax)) : 0.0;
           const double res = e - zp * (w64[k] / sum_w);
           corr[k] = (res > 0.0 ? res : 0.0) - e;
           sum_corr += corr[k];
@@ -371,11 +371,11 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
         for (int e = e0; e < e1; ++e) {
           const int64_t y = edge_index<T>(rs, e);
           const float t = load_elem<T>(row, y);
-          double v = t > -INFINITY ? exp(double(__fmul_rn(t, p.rT)) - double(smax)) : 0.0;
+          double v = t > -INFINITY ? exp64(double(__fmul_rn(t, p.rT)) - double(smax)) : 0.0;
           if (use_corr)
             for (int i = 0; i < count; ++i)
               if (qi[i] == y) {
-                const double res = v - zp * (exp(double(ql[i]) - ql0) / sum_w);
+                const double res = v - zp * (exp64(double(ql[i]) - ql0) / sum_w);
                 v = res > 0.0 ? res : 0.0;
                 break;
               }
@@ -407,8 +407,7 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
           float v[E];
           unpack<T>(load_vec(&rs.body[v0 + i]), v);
 #pragma unroll
-          for (int e = 0; e < E; ++e)
-            if (v[e] > -INFINITY) mine += exp(double(__fmul_rn(v[e], p.rT)) - double(smax));
+          for (int e = 0; e < E; ++e) mine += exp64(double(__fmul_rn(v[e], p.rT)) - double(smax));
         }
       }
       mine += sh.thread_corr[tid];
@@ -449,7 +448,7 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
           double v = 0.0;
           if (tid < kChunk && (y - rs.head) / E < rs.nvec) {
             const float t = load_elem<T>(row, y);
-            if (t > -INFINITY) v = exp(double(__fmul_rn(t, p.rT)) - double(smax));
+            if (t > -INFINITY) v = exp64(double(__fmul_rn(t, p.rT)) - double(smax));
             v += sh.chunk_corr[tid];
             if (v < 0.0) v = 0.0;
           }
@@ -485,30 +484,34 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
   }
 }
 
+// First rejected position of sequence b, or gamma when every draft token was accepted (block-wide).
+__device__ __forceinline__ int first_rejection(const VerifyParams& p, int64_t b, VerifyShared& sh) {
+  const int tid = threadIdx.x;
+  int jstar = p.gamma;
+  for (int j = tid; j < p.gamma; j += kBlock)
+    if (p.flags[b * p.gamma + j] != 1) { jstar = j; break; }
+#pragma unroll
+  for (int s = 32; s > 0; s >>= 1) { const int o = __shfl_xor(jstar, s, 64); jstar = o < jstar ? o : jstar; }
+  __syncthreads();
+  if (lane_id() == 0) sh.red.i[wave_id()] = jstar;
+  __syncthreads();
+  jstar = sh.red.i[0];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) jstar = sh.red.i[w] < jstar ? sh.red.i[w] : jstar;
+  __syncthreads();
+  return jstar;
+}
+
+// Kernel B1: fp64 sweep of the row to resample, one segment per workgroup.
 template <typename T>
-__global__ __launch_bounds__(kBlock) void verify_resample_kernel(const VerifyParams p) {
+__global__ __launch_bounds__(kBlock) void verify_sweep_kernel(const VerifyParams p) {
   constexpr int E = ElemTraits<T>::kPerVec;
   __shared__ VerifyShared sh;
   const int tid = threadIdx.x;
   const int n_seg_grid = p.n_seg_grid;      // workgroups per sequence (layout bound; rows may need fewer)
   const int64_t b = blockIdx.x / n_seg_grid;
   const int seg = int(blockIdx.x - b * n_seg_grid);
-  // first rejected position, or gamma for the bonus row
-  int jstar = p.gamma;
-  for (int j = tid; j < p.gamma; j += kBlock)
-    if (p.flags[b * p.gamma + j] != 1) { jstar = j; break; }
-  {
-    int m = jstar;
-#pragma unroll
-    for (int s = 32; s > 0; s >>= 1) { int o = __shfl_xor(m, s, 64); m = o < m ? o : m; }
-    __syncthreads();
-    if (lane_id() == 0) sh.red.i[wave_id()] = m;
-    __syncthreads();
-    jstar = sh.red.i[0];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) jstar = sh.red.i[w] < jstar ? sh.red.i[w] : jstar;
-    __syncthreads();
-  }
+  const int jstar = first_rejection(p, b, sh);
   const int broken = jstar < p.gamma && p.flags[b * p.gamma + jstar] == 2;
   const void* row = target_row<T>(p, b, jstar);
   const RowSplit rs = split_row<T>(row, p.V);
@@ -519,36 +522,42 @@ __global__ __launch_bounds__(kBlock) void verify_resample_kernel(const VerifyPar
     // ---- this workgroup's segment, held in registers: maximum first, then the fp64 sum -----------
     uint4 d[kSegVecs];
     const int64_t vbase = int64_t(seg) * kSegVecsTotal;
-    float smax = -INFINITY;
-    int bad = 0;
 #pragma unroll
     for (int i = 0; i < kSegVecs; ++i) {
       const int64_t vi = vbase + int64_t(i) * kBlock + tid;
       d[i] = neg_inf_vec<T>();
       if (vi < rs.nvec) d[i] = load_vec(&rs.body[vi]);
     }
+    float vmax = -INFINITY;
+    int bad = 0;
 #pragma unroll
     for (int i = 0; i < kSegVecs; ++i) {
       float v[E];
       unpack<T>(d[i], v);
 #pragma unroll
       for (int e = 0; e < E; ++e) {
-        if (v[e] != v[e] || v[e] == INFINITY) bad = 1;
-        smax = fmaxf(smax, __fmul_rn(v[e], p.rT));
+        bad |= (v[e] != v[e] || v[e] == INFINITY) ? 1 : 0;
+        vmax = fmaxf(vmax, v[e]);
       }
     }
-    smax = block_max_f32<kWaves>(smax, sh.red);
+    vmax = block_max_f32<kWaves>(vmax, sh.red);
     bad = __syncthreads_or(bad);
+    const float smax = __fmul_rn(vmax, p.rT);      // scaling is monotone: the largest s is at the largest t
     double sum = 0.0;
     if (smax > -INFINITY && !bad) {
+      const double m = double(smax);
+      double s0 = 0.0, s1 = 0.0;
 #pragma unroll
       for (int i = 0; i < kSegVecs; ++i) {
         float v[E];
         unpack<T>(d[i], v);
 #pragma unroll
-        for (int e = 0; e < E; ++e)
-          if (v[e] > -INFINITY) sum += exp(double(__fmul_rn(v[e], p.rT)) - double(smax));
+        for (int e = 0; e < E; e += 2) {            // -inf gives exactly 0
+          s0 += exp64(double(__fmul_rn(v[e], p.rT)) - m);
+          s1 += exp64(double(__fmul_rn(v[e + 1], p.rT)) - m);
+        }
       }
+      sum = s0 + s1;
     }
     sum = block_sum_f64<kWaves>(sum, sh.red);
     if (tid == 0) { segs[1 + seg].sum = sum; segs[1 + seg].smax = smax; segs[1 + seg].bad = bad; }
@@ -568,38 +577,45 @@ __global__ __launch_bounds__(kBlock) void verify_resample_kernel(const VerifyPar
       if (smax > -INFINITY && !bad)
         for (int e = e0; e < e1; ++e) {
           const float t = load_elem<T>(row, edge_index<T>(rs, e));
-          if (t > -INFINITY) sum += exp(double(__fmul_rn(t, p.rT)) - double(smax));
+          if (t > -INFINITY) sum += exp64(double(__fmul_rn(t, p.rT)) - double(smax));
         }
       SegResult& o = segs[piece == 0 ? 0 : n_seg_row + 1];
       o.sum = sum; o.smax = smax; o.bad = bad;
     }
   }
-  // ---- last workgroup of the sequence finishes it -------------------------------------------------
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const uint32_t done = atomicAdd(&p.counters[b], 1u);
-    sh.bcast_i[0] = done == uint32_t(n_seg_grid - 1) ? 1 : 0;
-  }
-  __syncthreads();
-  const int last = sh.bcast_i[0];
-  __syncthreads();
-  if (last) {
-    __threadfence();
-    resample_finish<T>(p, sh, b, jstar, row, rs, n_seg_row, broken);
-  }
 }
 
-template <typename T> hipError_t launch_verify(VerifyParams p, hipStream_t s) {
-  hipLaunchKernelGGL(verify_accept_kernel<T>, dim3(unsigned(p.B * p.gamma)), dim3(kBlock), 0, s, p);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const int E = ElemTraits<T>::kPerVec;
-  int n_seg = int((p.V / E + 1 + kSegVecsTotal - 1) / kSegVecsTotal);
-  if (n_seg > p.n_seg) n_seg = p.n_seg;
-  p.n_seg_grid = n_seg;
-  hipLaunchKernelGGL(verify_resample_kernel<T>, dim3(unsigned(p.B * n_seg)), dim3(kBlock), 0, s, p);
-  return hipGetLastError();
+// Kernel B2: one workgroup per sequence combines the segments and draws the token.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void verify_finish_kernel(const VerifyParams p) {
+  __shared__ VerifyShared sh;
+  const int64_t b = blockIdx.x;
+  const int jstar = first_rejection(p, b, sh);
+  const int broken = jstar < p.gamma && p.flags[b * p.gamma + jstar] == 2;
+  const void* row = target_row<T>(p, b, jstar);
+  const RowSplit rs = split_row<T>(row, p.V);
+  const int n_seg_row = int((rs.nvec + kSegVecsTotal - 1) / kSegVecsTotal);
+  resample_finish<T>(p, sh, b, jstar, row, rs, n_seg_row, broken);
+}
+
+// phases: bit 0 = kernel A (acceptance decisions), bit 1 = kernel B (resampling and outputs)
+template <typename T> hipError_t launch_verify(VerifyParams p, hipStream_t s, int phases) {
+  hipError_t e = hipSuccess;
+  if (phases & 1) {
+    hipLaunchKernelGGL(verify_accept_kernel<T>, dim3(unsigned(p.B * p.gamma)), dim3(kBlock), 0, s, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  if (phases & 2) {
+    const int E = ElemTraits<T>::kPerVec;
+    int n_seg = int((p.V / E + 1 + kSegVecsTotal - 1) / kSegVecsTotal);
+    if (n_seg > p.n_seg) n_seg = p.n_seg;
+    p.n_seg_grid = n_seg;
+    hipLaunchKernelGGL(verify_sweep_kernel<T>, dim3(unsigned(p.B * n_seg)), dim3(kBlock), 0, s, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(verify_finish_kernel<T>, dim3(unsigned(p.B)), dim3(kBlock), 0, s, p);
+    e = hipGetLastError();
+  }
+  return e;
 }
 
 }  // namespace tslt

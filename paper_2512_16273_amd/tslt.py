@@ -22,7 +22,7 @@ ROW_NONFINITE, ROW_EMPTY, ROW_TOKEN_NOT_IN_SET, ROW_EXACT_PATH = 1, 2, 4, 256
 MAX_K_CAP = 1024
 
 EXPORTS = ("tslt_version", "tslt_last_error", "tslt_workspace_bytes", "tslt_truncate", "tslt_sample",
-           "tslt_verify", "tslt_verify_tree")
+           "tslt_verify", "tslt_verify_accept", "tslt_verify_resample", "tslt_verify_tree")
 
 _lib = None
 
@@ -36,7 +36,7 @@ def load(path: Optional[str] = None):
     global _lib
     if _lib is not None and path is None:
         return _lib
-    path = path or LIB_PATH
+    path = path or os.environ.get("TSLT_LIBRARY") or LIB_PATH      # TSLT_LIBRARY: another build of the same ABI
     if not os.path.exists(path):
         raise TsltError(f"{path} not found: build it with `python -m paper_2512_16273_amd.build` "
                         "(there is no CPU fallback)")
@@ -53,9 +53,9 @@ def load(path: Optional[str] = None):
     lib.tslt_truncate.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tslt_sample.restype = c.c_int
     lib.tslt_sample.argtypes = [vp, vp, vp, i64, i32, vp, i32, i32, vp, vp, vp]
-    lib.tslt_verify.restype = c.c_int
-    lib.tslt_verify.argtypes = [vp, c.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp,
-                                vp, vp, sz, vp]
+    for fn in (lib.tslt_verify, lib.tslt_verify_accept, lib.tslt_verify_resample):
+        fn.restype = c.c_int
+        fn.argtypes = [vp, c.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tslt_verify_tree.restype = c.c_int
     lib.tslt_verify_tree.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, c.POINTER(i32), vp, vp, vp, i32, vp, vp,
                                      vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -159,10 +159,12 @@ def sample(idx: torch.Tensor, logit: torch.Tensor, count: torch.Tensor, u: torch
 
 def verify(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logit: torch.Tensor,
            q_count: torch.Tensor, draft_tokens: torch.Tensor, u_accept: torch.Tensor, u_resample: torch.Tensor,
-           out: Optional[dict] = None, workspace: Optional[torch.Tensor] = None) -> dict:
+           out: Optional[dict] = None, workspace: Optional[torch.Tensor] = None, phase: str = "both") -> dict:
     """tslt_verify: target [B, gamma+1, V]; sparse sets [B, gamma, k_cap]; returns accept_len [B],
-    tokens [B, gamma+1], ratio, beta [B, gamma], status [B]."""
+    tokens [B, gamma+1], ratio, beta [B, gamma], status [B].  phase = "accept" / "resample" calls
+    tslt_verify_accept / tslt_verify_resample (then `out` and `workspace` must be passed to both)."""
     lib = load()
+    fn = {"both": lib.tslt_verify, "accept": lib.tslt_verify_accept, "resample": lib.tslt_verify_resample}[phase]
     _dev(target, name="target")
     if target.dim() != 3:
         raise TsltError("target must be [B, gamma+1, V]")
@@ -183,11 +185,11 @@ def verify(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logi
                "status": torch.empty(B, dtype=torch.int32, device=dev)}
     need = workspace_bytes(OP_VERIFY, B, gamma, V, k_cap)
     ws = workspace if workspace is not None else _workspace(need, dev)
-    _check(lib.tslt_verify(_ptr(target), _dtype_code(target), B, gamma, V, target.stride(1), float(temperature),
-                           _ptr(q_idx), _ptr(q_logit), _ptr(q_count), k_cap, _ptr(draft_tokens), _ptr(u_accept),
-                           _ptr(u_resample), _ptr(out["accept_len"]), _ptr(out["tokens"]), _ptr(out.get("ratio")),
-                           _ptr(out.get("beta")), _ptr(out.get("status")), _ptr(ws), ws.numel() if ws is not None else 0,
-                           _stream()))
+    _check(fn(_ptr(target), _dtype_code(target), B, gamma, V, target.stride(1), float(temperature),
+              _ptr(q_idx), _ptr(q_logit), _ptr(q_count), k_cap, _ptr(draft_tokens), _ptr(u_accept),
+              _ptr(u_resample), _ptr(out["accept_len"]), _ptr(out["tokens"]), _ptr(out.get("ratio")),
+              _ptr(out.get("beta")), _ptr(out.get("status")), _ptr(ws), ws.numel() if ws is not None else 0,
+              _stream()))
     return out
 
 
