@@ -226,20 +226,66 @@ template <int NW> __device__ __forceinline__ int block_excl_scan_i32(int v, Bloc
   return base + inc - v;
 }
 
-// In-LDS bitonic sort, descending, of n (a power of two) 64-bit words by `nthreads` threads.
-__device__ __forceinline__ void bitonic_sort_desc(uint64_t* a, int n, int tid, int nthreads) {
-  for (int k = 2; k <= n; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int p = tid; p < (n >> 1); p += nthreads) {
-        int lo = ((p & ~(j - 1)) << 1) | (p & (j - 1));
-        int hi = lo | j;
-        bool desc = (lo & k) == 0;
-        uint64_t x = a[lo], y = a[hi];
-        if ((x < y) == desc) { a[lo] = y; a[hi] = x; }
-      }
-      __syncthreads();
+// Sort of n candidate records held in LDS, descending, by a 256-bin counting sort on the value
+// (bins divide the interval [min, max] of the values present evenly; any monotone binning keeps the
+// result exact) followed by an exact rank inside each bin.  The largest min(n, k_keep) records end up
+// in out[0..) in order.  `in` and `out` may be the same array; `tmp` (n records) must be distinct from
+// both.  hist, start and cursor are 256-entry LDS arrays.  Work per thread is about
+// n/256 * (1 + mean bin population); values crowded into one bin cost more, bounded by n^2/256
+// comparisons per thread.  Needs a 256-thread workgroup.
+__device__ __forceinline__ int value_bin(uint64_t c, double vmin, double scale) {
+  const int b = int((double(cand_value(c)) - vmin) * scale);
+  return b > 255 ? 255 : b;
+}
+__device__ __forceinline__ void bucket_sort_desc(const uint64_t* in, int n, uint64_t* tmp, uint64_t* out, int k_keep,
+                                                 uint32_t* hist, uint32_t* start, uint32_t* cursor, BlockScratch& red) {
+  if (n <= 0) return;
+  const int tid = threadIdx.x;
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  for (int i = tid; i < n; i += kBlock) {
+    const uint32_t k = uint32_t(in[i] >> 32);
+    kmin = k < kmin ? k : kmin;
+    kmax = k > kmax ? k : kmax;
+  }
+  kmax = wave_max_u32(kmax);
+  kmin = ~wave_max_u32(~kmin);
+  hist[tid] = 0;
+  if (lane_id() == 0) { red.i[wave_id()] = int(kmin); red.i[8 + wave_id()] = int(kmax); }
+  __syncthreads();
+  kmin = uint32_t(red.i[0]); kmax = uint32_t(red.i[8]);
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) {
+    kmin = uint32_t(red.i[w]) < kmin ? uint32_t(red.i[w]) : kmin;
+    kmax = uint32_t(red.i[8 + w]) > kmax ? uint32_t(red.i[8 + w]) : kmax;
+  }
+  const double vmin = double(key_to_f32(kmin));
+  const double span = double(key_to_f32(kmax)) - vmin;
+  const double scale = span > 0.0 ? 255.0 / span : 0.0;
+  for (int i = tid; i < n; i += kBlock) atomicAdd(&hist[value_bin(in[i], vmin, scale)], 1u);
+  __syncthreads();
+  int total;
+  const int excl = block_excl_scan_i32<kWaves>(int(hist[255 - tid]), red, total);   // bins in descending order
+  start[255 - tid] = uint32_t(excl);
+  cursor[255 - tid] = uint32_t(excl);
+  __syncthreads();
+  for (int i = tid; i < n; i += kBlock) {
+    const uint64_t c = in[i];
+    const uint32_t pos = atomicAdd(&cursor[value_bin(c, vmin, scale)], 1u);
+    tmp[pos] = c;
+  }
+  __syncthreads();
+  for (int i = tid; i < n; i += kBlock) {
+    const uint64_t c = tmp[i];
+    const int b = value_bin(c, vmin, scale);
+    const int s0 = int(start[b]);
+    if (s0 < k_keep) {
+      const int s1 = s0 + int(hist[b]);
+      int r = 0;
+      for (int j = s0; j < s1; ++j) r += tmp[j] > c ? 1 : 0;
+      if (s0 + r < k_keep) out[s0 + r] = c;
     }
   }
+  __syncthreads();
 }
 
 // How a row of V elements splits into a 16-byte aligned body of whole vectors plus at most

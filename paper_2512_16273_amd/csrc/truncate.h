@@ -29,7 +29,8 @@ struct TruncateParams {
   int jprime;        // rank (1-based) among the 256 per-thread sample maxima that gives tau0; 0 = always exact path
   int tau_bits;      // number of leading key bits resolved by the threshold search
   int wave_cap;      // capacity, in vectors, of one wave's hit buffer
-  int sort_cap;      // capacity of the candidate array (power of two)
+  int sort_cap;      // capacity of the candidate array
+  int region_a_bytes;  // size of the first dynamic-LDS region (hit buffers / sort scratch), multiple of 16
   int32_t* out_idx;
   float* out_logit;
   float* out_prob;
@@ -42,6 +43,7 @@ struct TruncateShared {
   BlockScratch red;
   uint32_t smax_key[kBlock];   // per-thread maxima of the sample, as keys
   uint32_t hist[256];
+  uint32_t cursor[256];
   int wave_count[kWaves];
   int cand_count;
   int bcast_i[4];
@@ -159,10 +161,12 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
   constexpr int E = ElemTraits<T>::kPerVec;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ TruncateShared sh;
-  // dynamic LDS: hit vectors, their vector indices, the candidate array
+  // dynamic LDS: region A holds the hit vectors and their vector indices during the pass and is the
+  // sort's scratch afterwards; region B is the candidate array
   uint4* grp_data = reinterpret_cast<uint4*>(dyn_lds);
   uint32_t* grp_vidx = reinterpret_cast<uint32_t*>(grp_data + kWaves * p.wave_cap);
-  uint64_t* cand = reinterpret_cast<uint64_t*>(grp_vidx + kWaves * p.wave_cap + ((kWaves * p.wave_cap) & 1));
+  uint64_t* sort_tmp = reinterpret_cast<uint64_t*>(dyn_lds);
+  uint64_t* cand = reinterpret_cast<uint64_t*>(dyn_lds + p.region_a_bytes);
 
   const int tid = threadIdx.x;
   const int lane = lane_id();
@@ -336,11 +340,8 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
   }
 
   // ---- sort the candidates into canonical order ------------------------------------------------
-  int n_sort = 64;
-  while (n_sort < n_cand) n_sort <<= 1;
-  for (int i = n_cand + tid; i < n_sort; i += kBlock) cand[i] = 0;
   __syncthreads();
-  if (n_cand > 1) bitonic_sort_desc(cand, n_sort, tid, kBlock);
+  bucket_sort_desc(cand, n_cand, sort_tmp, cand, p.k_sel, sh.hist, sh.smax_key, sh.cursor, sh.red);
   const int k_eff = n_cand < p.k_sel ? n_cand : p.k_sel;
 
   // ---- fp64 evaluation of the kept head: Top-rho, renormalisation, outputs -----------------------

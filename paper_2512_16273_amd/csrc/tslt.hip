@@ -46,7 +46,8 @@ int next_pow2(int v) {
 }
 
 // Launch plan of the truncate kernel: which rank among the per-thread sample maxima gives the
-// threshold, and how large the hit buffers and the candidate array have to be.
+// threshold, and how large the hit buffers and the candidate array have to be.  Returns the bytes of
+// dynamic LDS.
 size_t plan_truncate(tslt_dtype dt, int64_t V, tslt::TruncateParams& p) {
   const int E = dt == TSLT_BF16 ? 8 : 4;
   const double G = tslt::kBlock;
@@ -59,24 +60,32 @@ size_t plan_truncate(tslt_dtype dt, int64_t V, tslt::TruncateParams& p) {
   const double j = f >= 1.0 ? kp + 1.0 : kp + 4.0 * std::sqrt(kp) + 4.0;
   const double jc = G * (1.0 - std::exp(-j / G));      // distinct threads holding the top j
   int jprime = int(std::ceil(jc + 2.0 * std::sqrt(j > jc ? j - jc : 0.0) + 1.0));
+  auto layout = [&](int wave_cap, int sort_cap) {
+    size_t a = size_t(20) * tslt::kWaves * wave_cap;
+    if (a < size_t(8) * sort_cap) a = size_t(8) * sort_cap;
+    a = (a + 15) & ~size_t(15);
+    p.wave_cap = wave_cap; p.sort_cap = sort_cap; p.region_a_bytes = int(a);
+    return a + size_t(8) * sort_cap;
+  };
   p.tau_bits = dt == TSLT_BF16 ? 16 : 20;
   p.jprime = 0;
-  p.wave_cap = 1;
-  p.sort_cap = next_pow2(p.k_sel < 64 ? 64 : p.k_sel);
+  const int min_sort = p.k_sel < 64 ? 64 : p.k_sel;
+  size_t lds = layout(1, min_sort);
   if (jprime <= int(0.8 * G)) {
     const double j_eff = -G * std::log(1.0 - double(jprime) / G);
     const double cap_total = (j_eff + 4.0 * std::sqrt(j_eff) + 8.0) / f * 1.05;
     const int wave_cap = int(std::ceil(cap_total / tslt::kWaves * 1.3)) + 16;
-    int sort_cap = next_pow2(int(cap_total * 1.1) + 1);
-    if (sort_cap < p.sort_cap) sort_cap = p.sort_cap;
-    const size_t lds = size_t(20) * tslt::kWaves * wave_cap + 8 + size_t(8) * sort_cap;
-    if (lds + sizeof(tslt::TruncateShared) + 256 <= kMaxLds) {
+    int sort_cap = int(cap_total * 1.1) + 16;
+    if (sort_cap < min_sort) sort_cap = min_sort;
+    const size_t need = layout(wave_cap, sort_cap);
+    if (need + sizeof(tslt::TruncateShared) + 256 <= kMaxLds) {
       p.jprime = jprime;
-      p.wave_cap = wave_cap;
-      p.sort_cap = sort_cap;
+      lds = need;
+    } else {
+      lds = layout(1, min_sort);
     }
   }
-  return size_t(20) * tslt::kWaves * p.wave_cap + 8 + size_t(8) * p.sort_cap;
+  return lds;
 }
 
 template <typename K> hipError_t allow_large_lds(K kernel) {
