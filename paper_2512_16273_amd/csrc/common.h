@@ -229,17 +229,20 @@ template <int NW> __device__ __forceinline__ int block_excl_scan_i32(int v, Bloc
 // Sort of n candidate records held in LDS, descending, by a 256-bin counting sort on the value
 // (bins divide the interval [min, max] of the values present evenly; any monotone binning keeps the
 // result exact) followed by an exact rank inside each bin.  The largest min(n, k_keep) records end up
-// in out[0..) in order.  `in` and `out` may be the same array; `tmp` (n records) must be distinct from
-// both.  hist, start and cursor are 256-entry LDS arrays.  Work per thread is about
-// n/256 * (1 + mean bin population); values crowded into one bin cost more, bounded by n^2/256
-// comparisons per thread.  Needs a 256-thread workgroup.
+// in out[0..) in order.  Only the bins that can reach the first k_keep places are moved: `tmp` needs
+// room for k_keep records plus the population of the bin that straddles that boundary; the function
+// returns false, leaving `in` intact, when tmp_cap is too small for that.  `in` and `out` may be the
+// same array; `tmp` must be distinct from both.  hist, start and cursor are 256-entry LDS arrays.
+// Work per thread is about n/256 + k_keep/256 * mean bin population; values crowded into one bin cost
+// more, bounded by n^2/256 comparisons per thread.  Needs a 256-thread workgroup.
 __device__ __forceinline__ int value_bin(uint64_t c, double vmin, double scale) {
   const int b = int((double(cand_value(c)) - vmin) * scale);
   return b > 255 ? 255 : b;
 }
-__device__ __forceinline__ void bucket_sort_desc(const uint64_t* in, int n, uint64_t* tmp, uint64_t* out, int k_keep,
-                                                 uint32_t* hist, uint32_t* start, uint32_t* cursor, BlockScratch& red) {
-  if (n <= 0) return;
+__device__ __forceinline__ bool bucket_sort_desc(const uint64_t* in, int n, uint64_t* tmp, int tmp_cap, uint64_t* out,
+                                                 int k_keep, uint32_t* hist, uint32_t* start, uint32_t* cursor,
+                                                 BlockScratch& red) {
+  if (n <= 0) return true;
   const int tid = threadIdx.x;
   uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
   for (int i = tid; i < n; i += kBlock) {
@@ -260,32 +263,35 @@ __device__ __forceinline__ void bucket_sort_desc(const uint64_t* in, int n, uint
   }
   const double vmin = double(key_to_f32(kmin));
   const double span = double(key_to_f32(kmax)) - vmin;
-  const double scale = span > 0.0 ? 255.0 / span : 0.0;
+  const double scale = (span > 0.0 && span < 1e300) ? 255.0 / span : 0.0;
   for (int i = tid; i < n; i += kBlock) atomicAdd(&hist[value_bin(in[i], vmin, scale)], 1u);
   __syncthreads();
   int total;
-  const int excl = block_excl_scan_i32<kWaves>(int(hist[255 - tid]), red, total);   // bins in descending order
+  const int mine = int(hist[255 - tid]);
+  const int excl = block_excl_scan_i32<kWaves>(mine, red, total);   // bins in descending order
   start[255 - tid] = uint32_t(excl);
   cursor[255 - tid] = uint32_t(excl);
+  // records in the bins that start before place k_keep
+  const int n_moved = block_sum_i32<kWaves>(excl < k_keep ? mine : 0, red);
+  if (n_moved > tmp_cap) return false;
   __syncthreads();
   for (int i = tid; i < n; i += kBlock) {
     const uint64_t c = in[i];
-    const uint32_t pos = atomicAdd(&cursor[value_bin(c, vmin, scale)], 1u);
-    tmp[pos] = c;
+    const int b = value_bin(c, vmin, scale);
+    if (int(start[b]) < k_keep) tmp[atomicAdd(&cursor[b], 1u)] = c;
   }
   __syncthreads();
-  for (int i = tid; i < n; i += kBlock) {
+  for (int i = tid; i < n_moved; i += kBlock) {
     const uint64_t c = tmp[i];
     const int b = value_bin(c, vmin, scale);
     const int s0 = int(start[b]);
-    if (s0 < k_keep) {
-      const int s1 = s0 + int(hist[b]);
-      int r = 0;
-      for (int j = s0; j < s1; ++j) r += tmp[j] > c ? 1 : 0;
-      if (s0 + r < k_keep) out[s0 + r] = c;
-    }
+    const int s1 = s0 + int(hist[b]);
+    int r = 0;
+    for (int j = s0; j < s1; ++j) r += tmp[j] > c ? 1 : 0;
+    if (s0 + r < k_keep) out[s0 + r] = c;
   }
   __syncthreads();
+  return true;
 }
 
 // How a row of V elements splits into a 16-byte aligned body of whole vectors plus at most

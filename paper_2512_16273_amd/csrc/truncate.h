@@ -1,22 +1,25 @@
 // tslt_truncate: Top-K / Top-rho truncation of draft logits (Section 3.1) and compaction to the
 // sparse (index, logit) payload of Solution 1 (Section 3.2), one workgroup per row.
 //
-// One pass over the row.  A strided sample of tiles, kept in registers, gives a threshold tau0 that
-// a little more than K elements of the whole row are expected to exceed; the pass then does two
-// things per 16-byte vector: it adds exp2(z*k2 - c) to the row's fp32 partial sums (the softmax
-// normaliser, k2 = log2(e)/T, c a reference taken from the sample maximum), and it copies the
-// vector into an LDS buffer if any of its elements is above tau0.  If at least K elements were
-// above tau0 the top-K set is among them and is found exactly by sorting those candidates;
-// otherwise (ties, masked rows, unlucky sample, overflow of a buffer) the row is redone by an exact
-// radix selection that makes several passes.  Either way the kept entries are then evaluated in
-// fp64, which is also where Top-rho and the renormalisation are decided.
+// One pass over the row.  The row's tiles are visited in batches of kBatch tiles taken at equal
+// distances (tile b of every "quarter"), so that the first batch is a strided sample of the row.  From
+// that sample a threshold tau0 is chosen that a little more than K elements of the whole row are
+// expected to exceed.  The pass then does two things per 16-byte vector: it adds exp2(z*k2 - c) to the
+// row's fp32 partial sums (the softmax normaliser, k2 = log2(e)/T, c a reference taken from the
+// sample maximum), and, if any element of the vector is above tau0, it parks the vector in a small
+// per-wave LDS ring; rings are expanded into (value, index) candidate records when they fill up.  If
+// at least K elements were above tau0 the top-K set is among the candidates and is found exactly by
+// sorting them; otherwise (ties, masked rows, unlucky sample, overflow of a buffer) the row is redone
+// by an exact radix selection that makes several passes.  Either way the kept entries are then
+// evaluated in fp64, which is also where Top-rho and the renormalisation are decided.
 #pragma once
 #include "common.h"
 #include "exp64.h"
 
 namespace tslt {
 
-constexpr int kSampleTiles = 8;   // tiles of the row that form the threshold sample
+constexpr int kBatch = 4;      // tiles per batch; the first batch is the threshold sample
+constexpr int kRing = 64;      // pairs of vectors a wave can park; expanded when half full
 
 struct TruncateParams {
   const void* logits;
@@ -28,9 +31,8 @@ struct TruncateParams {
   int k_cap;
   int jprime;        // rank (1-based) among the 256 per-thread sample maxima that gives tau0; 0 = always exact path
   int tau_bits;      // number of leading key bits resolved by the threshold search
-  int wave_cap;      // capacity, in vectors, of one wave's hit buffer
   int sort_cap;      // capacity of the candidate array
-  int region_a_bytes;  // size of the first dynamic-LDS region (hit buffers / sort scratch), multiple of 16
+  int lds_recs;      // records that fit in the candidate region; those past the candidates are sort scratch
   int32_t* out_idx;
   float* out_logit;
   float* out_prob;
@@ -39,25 +41,28 @@ struct TruncateParams {
   int32_t* status;
 };
 
+// Dynamic LDS: [ rings ] [ candidates, then sort scratch ].  The ring space is
+// reused for the sort's three 256-entry tables and, before the pass, for the per-thread sample maxima.
+constexpr int kRingBytes = kWaves * kRing * 40;
+static_assert(kRingBytes >= 3 * 256 * 4, "ring space must hold the sort tables");
+inline size_t truncate_lds_bytes(int lds_recs) { return size_t(kRingBytes) + size_t(8) * lds_recs; }
+
 struct TruncateShared {
   BlockScratch red;
-  uint32_t smax_key[kBlock];   // per-thread maxima of the sample, as keys
-  uint32_t hist[256];
-  uint32_t cursor[256];
-  int wave_count[kWaves];
   int cand_count;
+  int overflow;
   int bcast_i[4];
   double bcast_d[2];
 };
 
 // ---------------------------------------------------------------------------------------------
-// Exact multi-pass selection: the k_eff largest elements of the row in the canonical order, found
+// Exact multi-pass selection, the last resort: the k_eff largest elements of the row in the canonical order, found
 // by a 4x8-bit radix search for the k-th largest key and an index-ordered collection of the ties.
 // Also recomputes the fp32 sum with the true maximum as reference.  Returns the number of
 // candidates written to cand[] (exactly k_eff), or 0 with `st` set.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-__device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uint64_t* cand,
+__device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uint64_t* cand, uint32_t* hist,
                             TruncateShared& sh, float& c_ref, double& z_c, int& st) {
   const int tid = threadIdx.x;
   // pass 1: validity, number of selectable elements, maximum
@@ -79,19 +84,19 @@ __device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uin
   uint32_t prefix = 0;
   int need = k_eff;
   for (int shift = 24; shift >= 0; shift -= 8) {
-    sh.hist[tid] = 0;
+    hist[tid] = 0;
     __syncthreads();
     const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
     for (int64_t i = tid; i < V; i += kBlock) {
       float v = load_elem<T>(row, i);
       uint32_t key = mono_key(v + 0.0f);
-      if (v > -INFINITY && (key & hi_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
+      if (v > -INFINITY && (key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
     }
     __syncthreads();
     if (tid == 0) {
       int cum = 0, d = 255;
       for (; d > 0; --d) {
-        int h = int(sh.hist[d]);
+        int h = int(hist[d]);
         if (cum + h >= need) break;
         cum += h;
       }
@@ -156,17 +161,169 @@ __device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uin
 }
 
 // ---------------------------------------------------------------------------------------------
+// ---------------------------------------------------------------------------------------------
+// Two-pass selection, the first fallback.  Pass 1 takes the maximum of 1024 disjoint groups of the
+// row (4 per thread); the k-th largest of those maxima is a threshold that at least k elements reach,
+// so the top-k set is among the elements >= it, of which there are only a few more than k unless the
+// row is full of ties.  Pass 2 collects them.  Returns the number of candidates, 0 with `st` set for
+// an unusable row, or -1 when the candidates do not fit (then the radix selection is used).
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, float k2, uint64_t* cand, int cap,
+                               int lds_recs, uint32_t* tables, TruncateShared& sh, bool need_sum, float& c_ref,
+                               double& z_c, int& st) {
+  constexpr int E = ElemTraits<T>::kPerVec;
+  const int tid = threadIdx.x;
+  const int n_edge = rs.head + rs.tail;
+  const int64_t n_tiles = (rs.nvec + kBlock - 1) / kBlock;
+  if (cap < 4 * kBlock + 2 * E) return -1;
+  // pass 1
+  float gmax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  int fin = 0, bad = 0;
+  for (int64_t t0 = 0; t0 < n_tiles; t0 += 4) {
+    uint4 d[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t vi = (t0 + u) * kBlock + tid;
+      d[u] = neg_inf_vec<T>();
+      if (vi < rs.nvec) d[u] = load_vec(&rs.body[vi]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float v[E];
+      unpack<T>(d[u], v);
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        bad |= (v[e] != v[e] || v[e] == INFINITY) ? 1 : 0;
+        fin += v[e] > -INFINITY ? 1 : 0;
+        gmax[u] = fmaxf(gmax[u], v[e]);
+      }
+    }
+  }
+  float edge_v = -INFINITY;
+  int64_t edge_i = 0;
+  if (tid < n_edge) {
+    edge_i = edge_index<T>(rs, tid);
+    edge_v = load_elem<T>(row, edge_i);
+    bad |= (edge_v != edge_v || edge_v == INFINITY) ? 1 : 0;
+    fin += edge_v > -INFINITY ? 1 : 0;
+  }
+  bad = block_or_i32<kWaves>(bad, sh.red);
+  fin = block_sum_i32<kWaves>(fin, sh.red);
+  if (bad) { st |= 1; return 0; }
+  if (fin == 0) { st |= 2; return 0; }
+  const int k_eff = k_sel < fin ? k_sel : fin;
+  float vmax = fmaxf(fmaxf(gmax[0], gmax[1]), fmaxf(gmax[2], gmax[3]));
+  vmax = block_max_f32<kWaves>(fmaxf(vmax, edge_v), sh.red);
+  // the k_eff-th largest group maximum (edge elements are groups of their own; empty groups are left out)
+  if (tid == 0) sh.cand_count = 0;
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (gmax[u] > -INFINITY) cand[atomicAdd(&sh.cand_count, 1)] = make_cand(gmax[u], uint32_t(tid * 4 + u));
+  if (tid < n_edge && edge_v > -INFINITY) cand[atomicAdd(&sh.cand_count, 1)] = make_cand(edge_v, uint32_t(4 * kBlock + tid));
+  __syncthreads();
+  const int n_groups = sh.cand_count;
+  float tau = -INFINITY;                               // fewer than k_eff non-empty groups: take everything
+  if (n_groups >= k_eff) {
+    if (!bucket_sort_desc(cand, n_groups, cand + n_groups, lds_recs - n_groups, cand, k_eff, tables, tables + 256,
+                          tables + 512, sh.red))
+      return -1;
+    tau = cand_value(cand[k_eff - 1]);
+  }
+  __syncthreads();
+  // pass 2
+  if (tid == 0) sh.cand_count = 0;
+  __syncthreads();
+  if (need_sum) c_ref = __fmul_rn(vmax, k2);
+  float acc = 0.f;
+  for (int64_t t0 = 0; t0 < n_tiles; t0 += 4) {
+    uint4 d[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t vi = (t0 + u) * kBlock + tid;
+      d[u] = neg_inf_vec<T>();
+      if (vi < rs.nvec) d[u] = load_vec(&rs.body[vi]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float v[E];
+      unpack<T>(d[u], v);
+      const uint32_t base = uint32_t(rs.head) + uint32_t((t0 + u) * kBlock + tid) * E;
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        if (need_sum) acc += fast_exp2(__builtin_fmaf(v[e], k2, -c_ref));
+        if (v[e] >= tau && v[e] > -INFINITY) {
+          const int pos = atomicAdd(&sh.cand_count, 1);
+          if (pos < cap) cand[pos] = make_cand(v[e], base + e);
+        }
+      }
+    }
+  }
+  if (tid < n_edge) {
+    if (need_sum) acc += fast_exp2(__builtin_fmaf(edge_v, k2, -c_ref));
+    if (edge_v >= tau && edge_v > -INFINITY) {
+      const int pos = atomicAdd(&sh.cand_count, 1);
+      if (pos < cap) cand[pos] = make_cand(edge_v, uint32_t(edge_i));
+    }
+  }
+  if (need_sum) z_c = block_sum_f64<kWaves>(double(acc), sh.red);
+  __syncthreads();
+  const int n = sh.cand_count;
+  __syncthreads();
+  return n <= cap ? n : -1;
+}
+
+// A ring slot holds a pair of 16-byte vectors of which at least one element is above tau0, and the
+// index (in vectors, within the row's aligned body) of each.
+struct RingPair { uint4 w[2]; };
+
+// Expands the hit pairs parked in a wave's ring into candidate records (elements above tau0).
+template <typename T>
+__device__ __forceinline__ void expand_ring(const RingPair* ring, const uint2* ring_vidx, int n, float tau0,
+                                            uint32_t head, uint64_t* cand, int cap, TruncateShared& sh) {
+  constexpr int E = ElemTraits<T>::kPerVec;
+  const int lane = lane_id();
+  if (lane < n) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      float v[E];
+      unpack<T>(ring[lane].w[h], v);
+      const uint32_t base = head + (h == 0 ? ring_vidx[lane].x : ring_vidx[lane].y) * E;
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        if (v[e] > tau0) {
+          const int pos = atomicAdd(&sh.cand_count, 1);
+          if (pos < cap) cand[pos] = make_cand(v[e], base + e);
+        }
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ float max3f(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+template <typename T> __device__ __forceinline__ float vec_max(const float (&v)[ElemTraits<T>::kPerVec]);
+template <> __device__ __forceinline__ float vec_max<float>(const float (&v)[4]) {
+  return max3f(max3f(v[0], v[1], v[2]), v[3], v[3]);
+}
+template <> __device__ __forceinline__ float vec_max<Bf16>(const float (&v)[8]) {
+  return max3f(max3f(max3f(v[0], v[1], v[2]), v[3], v[4]), max3f(v[5], v[6], v[7]), v[5]);
+}
+
 template <typename T>
 __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p) {
   constexpr int E = ElemTraits<T>::kPerVec;
+  static_assert(kBatch == 4, "the pass handles a batch as two pairs of tiles");
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ TruncateShared sh;
-  // dynamic LDS: region A holds the hit vectors and their vector indices during the pass and is the
-  // sort's scratch afterwards; region B is the candidate array
-  uint4* grp_data = reinterpret_cast<uint4*>(dyn_lds);
-  uint32_t* grp_vidx = reinterpret_cast<uint32_t*>(grp_data + kWaves * p.wave_cap);
-  uint64_t* sort_tmp = reinterpret_cast<uint64_t*>(dyn_lds);
-  uint64_t* cand = reinterpret_cast<uint64_t*>(dyn_lds + p.region_a_bytes);
+  RingPair* ring_all = reinterpret_cast<RingPair*>(dyn_lds);
+  uint2* ring_vidx_all = reinterpret_cast<uint2*>(dyn_lds + kWaves * kRing * 32);
+  uint32_t* tables = reinterpret_cast<uint32_t*>(dyn_lds);          // 3 x 256 entries, aliasing the rings
+  uint64_t* cand = reinterpret_cast<uint64_t*>(dyn_lds + kRingBytes);
 
   const int tid = threadIdx.x;
   const int lane = lane_id();
@@ -175,43 +332,51 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
   const void* row = reinterpret_cast<const char*>(p.logits) + size_t(row_i) * size_t(p.row_stride) * ElemTraits<T>::kBytes;
   const RowSplit rs = split_row<T>(row, p.V);
   const int n_edge = rs.head + rs.tail;
-  const int64_t n_tiles = (rs.nvec + kBlock - 1) / kBlock;
+  const uint32_t nvec = uint32_t(rs.nvec);
+  const uint32_t n_tiles = (nvec + kBlock - 1) / kBlock;
+  const uint32_t n_full = nvec / (kBatch * kBlock);        // batches of kBatch complete, consecutive tiles
+  // The sample: the first tile of kBatch batches at equal distances; a row with fewer than 4*kBatch
+  // complete batches uses its first kBatch tiles.
+  const bool long_row = n_full >= 4;
+  const uint32_t s_stride = long_row ? (n_full / 4) * kBatch : 1;   // in tiles
 
   int st = 0;
   int n_cand = 0;
   float c_ref = 0.0f;
   double z_c = 0.0;
   bool fast_ok = p.jprime > 0 && n_tiles > 0;
+  if (tid == 0) { sh.cand_count = 0; sh.overflow = 0; }
 
   if (fast_ok) {
-    // ---- sample tiles into registers ------------------------------------------------------
-    const int ns = n_tiles < kSampleTiles ? int(n_tiles) : kSampleTiles;
-    uint4 smp[kSampleTiles];
-    float tmax = -INFINITY;
+    // ---- the sample: per-thread maxima ----------------------------------------------------------
+    uint4 d[kBatch];
+    if (long_row) {
 #pragma unroll
-    for (int k = 0; k < kSampleTiles; ++k) {
-      smp[k] = neg_inf_vec<T>();
-      if (k < ns) {
-        int64_t vi = ((int64_t(k) * n_tiles) / ns) * kBlock + tid;
-        if (vi < rs.nvec) smp[k] = load_vec_stream(&rs.body[vi]);
+      for (int u = 0; u < kBatch; ++u) d[u] = load_vec_stream(&rs.body[u * s_stride * kBlock + tid]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const uint32_t vi = u * kBlock + tid;
+        d[u] = neg_inf_vec<T>();
+        if (vi < nvec) d[u] = load_vec_stream(&rs.body[vi]);
       }
     }
+    float tmax = -INFINITY;
 #pragma unroll
-    for (int k = 0; k < kSampleTiles; ++k) {
+    for (int u = 0; u < kBatch; ++u) {
       float v[E];
-      unpack<T>(smp[k], v);
-#pragma unroll
-      for (int e = 0; e < E; ++e) tmax = fmaxf(tmax, v[e]);
+      unpack<T>(d[u], v);
+      tmax = fmaxf(tmax, vec_max<T>(v));
     }
-    sh.smax_key[tid] = mono_key(tmax);
+    tables[tid] = mono_key(tmax);
     __syncthreads();
     // ---- tau0: the jprime-th largest of the 256 per-thread sample maxima (every wave redundantly)
     uint32_t kq[kWaves];
 #pragma unroll
-    for (int q = 0; q < kWaves; ++q) kq[q] = sh.smax_key[lane + 64 * q];
+    for (int q = 0; q < kWaves; ++q) kq[q] = tables[lane + 64 * q];
     uint32_t tau_key = 0;
     for (int bit = 31; bit >= 32 - p.tau_bits; --bit) {
-      uint32_t trial = tau_key | (1u << bit);
+      const uint32_t trial = tau_key | (1u << bit);
       int cnt = 0;
 #pragma unroll
       for (int q = 0; q < kWaves; ++q) cnt += __popcll(ballot(kq[q] >= trial));
@@ -225,123 +390,134 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
     const float tau0 = tau_key <= kKeyNegInf ? -INFINITY : key_to_f32(tau_key);
     fast_ok = smax > -INFINITY && smax < INFINITY;   // false for NaN too
     c_ref = __fmul_rn(smax, p.k2);
-    const float neg_c = -c_ref;
-    const float k2 = p.k2;
-
-    // ---- the pass ---------------------------------------------------------------------------
-    float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
-    int wave_cnt = 0;
-    uint4* my_data = grp_data + wave * p.wave_cap;
-    uint32_t* my_vidx = grp_vidx + wave * p.wave_cap;
-    const int wave_cap = p.wave_cap;
-
-    auto process = [&](const uint4& w, uint32_t vidx) {
-      float v[E];
-      unpack<T>(w, v);
-      float mx = v[0];
-#pragma unroll
-      for (int e = 1; e < E; ++e) mx = fmaxf(mx, v[e]);
-#pragma unroll
-      for (int e = 0; e < E; e += 4) {
-        acc0 += fast_exp2(__builtin_fmaf(v[e + 0], k2, neg_c));
-        acc1 += fast_exp2(__builtin_fmaf(v[e + 1], k2, neg_c));
-        acc2 += fast_exp2(__builtin_fmaf(v[e + 2], k2, neg_c));
-        acc3 += fast_exp2(__builtin_fmaf(v[e + 3], k2, neg_c));
-      }
-      const bool hit = mx > tau0;
-      const uint64_t mask = ballot(hit);
-      if (mask != 0) {
-        const int pos = wave_cnt + lanes_below(mask);
-        if (hit && pos < wave_cap) {
-          my_data[pos] = w;
-          my_vidx[pos] = vidx;
-        }
-        wave_cnt += __popcll(mask);
-      }
-    };
+    __syncthreads();                                  // the maxima are read; the space becomes the rings
 
     if (fast_ok) {
+      // ---- the pass -------------------------------------------------------------------------
+      const float neg_c = -c_ref;
+      const float k2 = p.k2;
+      float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+      int wave_cnt = 0;                                // pairs parked in this wave's ring
+      int lost = 0;
+      RingPair* ring = ring_all + wave * kRing;
+      uint2* ring_vidx = ring_vidx_all + wave * kRing;
+      const uint32_t head = uint32_t(rs.head);
+
+      // Two vectors at a time: their exp2 terms go to the partial sums; if any of their elements is
+      // above tau0 the pair is parked in the ring, which is expanded when it is half full.
+      auto process_pair = [&](const uint4& w0, const uint4& w1, uint32_t vidx0, uint32_t vidx1) {
+        float a[E], b[E];
+        unpack<T>(w0, a);
+        unpack<T>(w1, b);
+        const float mx = fmaxf(vec_max<T>(a), vec_max<T>(b));
 #pragma unroll
-      for (int k = 0; k < kSampleTiles; ++k) {
-        if (k < ns) {
-          int64_t vi = ((int64_t(k) * n_tiles) / ns) * kBlock + tid;
-          process(smp[k], uint32_t(vi));
-        }
-      }
-      constexpr int U = 4;
-      int next_k = 0;
-      int64_t next_sample = 0;   // tile index of sample tile next_k
-      for (int64_t t0 = 0; t0 < n_tiles; t0 += U) {
-        uint4 d[U];
-        bool use[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int64_t t = t0 + u;
-          bool is_sample = false;
-          if (next_k < ns && t == next_sample) {
-            is_sample = true;
-            ++next_k;
-            next_sample = next_k < ns ? (int64_t(next_k) * n_tiles) / ns : -1;
-          }
-          use[u] = t < n_tiles && !is_sample;
-          d[u] = neg_inf_vec<T>();
-          const int64_t vi = t * kBlock + tid;
-          if (use[u] && vi < rs.nvec) d[u] = load_vec_stream(&rs.body[vi]);
+        for (int e = 0; e < E; e += 4) {
+          acc0 += fast_exp2(__builtin_fmaf(a[e + 0], k2, neg_c));
+          acc1 += fast_exp2(__builtin_fmaf(a[e + 1], k2, neg_c));
+          acc2 += fast_exp2(__builtin_fmaf(a[e + 2], k2, neg_c));
+          acc3 += fast_exp2(__builtin_fmaf(a[e + 3], k2, neg_c));
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          if (use[u]) process(d[u], uint32_t((t0 + u) * kBlock + tid));
+        for (int e = 0; e < E; e += 4) {
+          acc0 += fast_exp2(__builtin_fmaf(b[e + 0], k2, neg_c));
+          acc1 += fast_exp2(__builtin_fmaf(b[e + 1], k2, neg_c));
+          acc2 += fast_exp2(__builtin_fmaf(b[e + 2], k2, neg_c));
+          acc3 += fast_exp2(__builtin_fmaf(b[e + 3], k2, neg_c));
         }
-      }
-      // edge elements (row not 16-byte aligned, or V not a whole number of vectors)
-      float edge_v = -INFINITY;
-      int64_t edge_i = 0;
-      if (tid < n_edge) {
-        edge_i = edge_index<T>(rs, tid);
-        edge_v = load_elem<T>(row, edge_i);
-        acc0 += fast_exp2(__builtin_fmaf(edge_v, k2, neg_c));
-      }
-      z_c = block_sum_f64<kWaves>(double(acc0) + double(acc1) + double(acc2) + double(acc3), sh.red);
-      if (lane == 0) sh.wave_count[wave] = wave_cnt;
-      if (tid == 0) sh.cand_count = 0;
-      __syncthreads();
-      bool overflow = false;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) overflow = overflow || sh.wave_count[w] > wave_cap;
-      // ---- expand the hit vectors into candidate records -----------------------------------
-      if (!overflow) {
-        for (int g = lane; g < wave_cnt; g += 64) {
-          float v[E];
-          unpack<T>(my_data[g], v);
-          const uint32_t base = uint32_t(rs.head) + my_vidx[g] * E;
-#pragma unroll
-          for (int e = 0; e < E; ++e) {
-            if (v[e] > tau0) {
-              int pos = atomicAdd(&sh.cand_count, 1);
-              if (pos < p.sort_cap) cand[pos] = make_cand(v[e], base + e);
+        const bool hit = mx > tau0;
+        const uint64_t mask = ballot(hit);
+        if (mask != 0) {
+          const int pos = wave_cnt + lanes_below(mask);
+          if (hit) {
+            if (pos < kRing) {
+              ring[pos].w[0] = w0;
+              ring[pos].w[1] = w1;
+              ring_vidx[pos] = make_uint2(vidx0, vidx1);
+            } else {
+              lost = 1;
             }
           }
+          wave_cnt += __popcll(mask);
+          if (wave_cnt > kRing / 2) {                  // wave-uniform
+            expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh);
+            wave_cnt = 0;
+          }
         }
-        if (tid < n_edge && edge_v > tau0) {
-          int pos = atomicAdd(&sh.cand_count, 1);
+      };
+
+      // the sample tiles, already in registers
+      {
+        const uint32_t t1 = s_stride, t2 = 2 * s_stride, t3 = 3 * s_stride;
+        process_pair(d[0], d[1], tid, t1 * kBlock + tid);
+        process_pair(d[2], d[3], t2 * kBlock + tid, t3 * kBlock + tid);
+      }
+      uint32_t first_generic_tile = kBatch;             // short rows: everything after the sample tiles
+      if (long_row) {
+        // complete batches; the first tile of a batch is left out when it was a sample tile
+        uint32_t skip_b = 0, skips_left = kBatch;
+        const uint32_t stride_b = s_stride / kBatch;
+        const uint4* src = rs.body + tid;
+        for (uint32_t b = 0; b < n_full; ++b, src += kBatch * kBlock) {
+          const bool skip = skips_left > 0 && b == skip_b;
+          if (skip) { skip_b += stride_b; --skips_left; }
+          d[0] = neg_inf_vec<T>();
+          if (!skip) d[0] = load_vec_stream(src);
+          d[1] = load_vec_stream(src + kBlock);
+          d[2] = load_vec_stream(src + 2 * kBlock);
+          d[3] = load_vec_stream(src + 3 * kBlock);
+          const uint32_t v0 = b * (kBatch * kBlock) + tid;
+          process_pair(d[0], d[1], v0, v0 + kBlock);
+          process_pair(d[2], d[3], v0 + 2 * kBlock, v0 + 3 * kBlock);
+        }
+        first_generic_tile = n_full * kBatch;
+      }
+      // what is left: tiles that may be incomplete
+      for (uint32_t t = first_generic_tile; t < n_tiles; t += 2) {
+        const uint32_t v0 = t * kBlock + tid, v1 = v0 + kBlock;
+        d[0] = neg_inf_vec<T>();
+        d[1] = neg_inf_vec<T>();
+        if (v0 < nvec) d[0] = load_vec_stream(&rs.body[v0]);
+        if (v1 < nvec) d[1] = load_vec_stream(&rs.body[v1]);
+        process_pair(d[0], d[1], v0, v1);
+      }
+      expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh);
+      if (lost) sh.overflow = 1;
+      // edge elements (row not 16-byte aligned, or V not a whole number of vectors)
+      if (tid < n_edge) {
+        const int64_t edge_i = edge_index<T>(rs, tid);
+        const float edge_v = load_elem<T>(row, edge_i);
+        acc0 += fast_exp2(__builtin_fmaf(edge_v, k2, neg_c));
+        if (edge_v > tau0) {
+          const int pos = atomicAdd(&sh.cand_count, 1);
           if (pos < p.sort_cap) cand[pos] = make_cand(edge_v, uint32_t(edge_i));
         }
       }
+      z_c = block_sum_f64<kWaves>(double(acc0) + double(acc1) + double(acc2) + double(acc3), sh.red);
       __syncthreads();
       n_cand = sh.cand_count;
-      fast_ok = !overflow && n_cand <= p.sort_cap && n_cand >= p.k_sel && z_c > 0.0 && z_c < INFINITY;
+      fast_ok = !sh.overflow && n_cand <= p.sort_cap && n_cand >= p.k_sel && z_c > 0.0 && z_c < INFINITY;
       __syncthreads();
     }
   }
 
   if (!fast_ok) {
     st |= 256;
-    n_cand = exact_select<T>(row, p.V, p.k_sel, p.k2, cand, sh, c_ref, z_c, st);
+    const bool need_sum = !(z_c > 0.0 && z_c < INFINITY);
+    n_cand = two_pass_select<T>(row, rs, p.k_sel, p.k2, cand, p.sort_cap, p.lds_recs, tables, sh, need_sum, c_ref, z_c, st);
+    if (n_cand < 0) n_cand = exact_select<T>(row, p.V, p.k_sel, p.k2, cand, tables, sh, c_ref, z_c, st);
   }
 
   // ---- sort the candidates into canonical order ------------------------------------------------
   __syncthreads();
-  bucket_sort_desc(cand, n_cand, sort_tmp, cand, p.k_sel, sh.hist, sh.smax_key, sh.cursor, sh.red);
+  if (!bucket_sort_desc(cand, n_cand, cand + n_cand, p.lds_recs - n_cand, cand, p.k_sel, tables, tables + 256,
+                        tables + 512, sh.red)) {
+    // the bin at the k-th place is too crowded for the scratch space (a row full of ties): radix selection
+    // delivers exactly k candidates, which always fit
+    st |= 256;
+    n_cand = exact_select<T>(row, p.V, p.k_sel, p.k2, cand, tables, sh, c_ref, z_c, st);
+    bucket_sort_desc(cand, n_cand, cand + n_cand, p.lds_recs - n_cand, cand, p.k_sel, tables, tables + 256, tables + 512,
+                     sh.red);
+  }
   const int k_eff = n_cand < p.k_sel ? n_cand : p.k_sel;
 
   // ---- fp64 evaluation of the kept head: Top-rho, renormalisation, outputs -----------------------

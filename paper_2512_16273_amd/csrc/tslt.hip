@@ -46,46 +46,38 @@ int next_pow2(int v) {
 }
 
 // Launch plan of the truncate kernel: which rank among the per-thread sample maxima gives the
-// threshold, and how large the hit buffers and the candidate array have to be.  Returns the bytes of
-// dynamic LDS.
+// threshold, and how large the candidate array has to be.  Returns the bytes of dynamic LDS.
 size_t plan_truncate(tslt_dtype dt, int64_t V, tslt::TruncateParams& p) {
   const int E = dt == TSLT_BF16 ? 8 : 4;
   const double G = tslt::kBlock;
   const int64_t tile = int64_t(tslt::kBlock) * E;
   const int64_t n_tiles = (V + tile - 1) / tile;
-  const int64_t ns = n_tiles < tslt::kSampleTiles ? n_tiles : tslt::kSampleTiles;
+  const int64_t ns = n_tiles < tslt::kBatch ? n_tiles : tslt::kBatch;
   const double n_sample = double(ns * tile < V ? ns * tile : V);
-  const double f = n_sample / double(V);
+  const double f = n_sample / double(V);               // fraction of the row in the sample
   const double kp = p.k_sel * f;                       // expected sample elements inside the top-k
   const double j = f >= 1.0 ? kp + 1.0 : kp + 4.0 * std::sqrt(kp) + 4.0;
   const double jc = G * (1.0 - std::exp(-j / G));      // distinct threads holding the top j
-  int jprime = int(std::ceil(jc + 2.0 * std::sqrt(j > jc ? j - jc : 0.0) + 1.0));
-  auto layout = [&](int wave_cap, int sort_cap) {
-    size_t a = size_t(20) * tslt::kWaves * wave_cap;
-    if (a < size_t(8) * sort_cap) a = size_t(8) * sort_cap;
-    a = (a + 15) & ~size_t(15);
-    p.wave_cap = wave_cap; p.sort_cap = sort_cap; p.region_a_bytes = int(a);
-    return a + size_t(8) * sort_cap;
-  };
+  const int jprime = int(std::ceil(jc + 2.0 * std::sqrt(j > jc ? j - jc : 0.0) + 1.0));
   p.tau_bits = dt == TSLT_BF16 ? 16 : 20;
   p.jprime = 0;
-  const int min_sort = p.k_sel < 64 ? 64 : p.k_sel;
-  size_t lds = layout(1, min_sort);
+  // candidate capacity: always room for the fallback's 1024 group maxima; the sort needs k_sel more
+  // records of scratch behind the candidates plus room for the bin that straddles the k-th place
+  const int min_cap = (4 * tslt::kBlock + 16 > 2 * p.k_sel) ? 4 * tslt::kBlock + 16 : 2 * p.k_sel;
+  const int scratch = p.k_sel + p.k_sel / 2 + 64;
+  p.sort_cap = min_cap;
+  p.lds_recs = min_cap + scratch;
   if (jprime <= int(0.8 * G)) {
     const double j_eff = -G * std::log(1.0 - double(jprime) / G);
-    const double cap_total = (j_eff + 4.0 * std::sqrt(j_eff) + 8.0) / f * 1.05;
-    const int wave_cap = int(std::ceil(cap_total / tslt::kWaves * 1.3)) + 16;
-    int sort_cap = int(cap_total * 1.1) + 16;
-    if (sort_cap < min_sort) sort_cap = min_sort;
-    const size_t need = layout(wave_cap, sort_cap);
-    if (need + sizeof(tslt::TruncateShared) + 256 <= kMaxLds) {
+    int sort_cap = int((j_eff + 5.0 * std::sqrt(j_eff) + 4.0) / f) + 16;   // mean + 5 sigma of the hits
+    if (sort_cap < min_cap) sort_cap = min_cap;
+    if (tslt::truncate_lds_bytes(sort_cap + scratch) + sizeof(tslt::TruncateShared) + 256 <= kMaxLds) {
       p.jprime = jprime;
-      lds = need;
-    } else {
-      lds = layout(1, min_sort);
+      p.sort_cap = sort_cap;
+      p.lds_recs = sort_cap + scratch;
     }
   }
-  return lds;
+  return tslt::truncate_lds_bytes(p.lds_recs);
 }
 
 template <typename K> hipError_t allow_large_lds(K kernel) {
