@@ -84,6 +84,13 @@ __device__ __forceinline__ uint4 load_vec(const uint4* p) {
   return make_uint4(r.x, r.y, r.z, r.w);
 }
 
+// max of three without the NaN-quieting moves the compiler adds around fmaxf (NaNs are found by other means)
+__device__ __forceinline__ float max3f(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }

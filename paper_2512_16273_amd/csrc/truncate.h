@@ -19,7 +19,7 @@
 namespace tslt {
 
 constexpr int kBatch = 4;      // tiles per batch; the first batch is the threshold sample
-constexpr int kRing = 64;      // pairs of vectors a wave can park; expanded when half full
+constexpr int kRing = 48;      // pairs of vectors a wave can park; expanded when a third full
 
 struct TruncateParams {
   const void* logits;
@@ -32,7 +32,9 @@ struct TruncateParams {
   int jprime;        // rank (1-based) among the 256 per-thread sample maxima that gives tau0; 0 = always exact path
   int tau_bits;      // number of leading key bits resolved by the threshold search
   int sort_cap;      // capacity of the candidate array
-  int lds_recs;      // records that fit in the candidate region; those past the candidates are sort scratch
+  int lds_recs;      // records that fit in the candidate region; those past sort_cap are sort scratch
+  int ring_bytes;    // size of the ring space at the start of dynamic LDS (>= kRingBytes)
+  int tmp_in_ring;   // the sort scratch is the ring space behind the tables
   int32_t* out_idx;
   float* out_logit;
   float* out_prob;
@@ -43,9 +45,11 @@ struct TruncateParams {
 
 // Dynamic LDS: [ rings ] [ candidates, then sort scratch ].  The ring space is
 // reused for the sort's three 256-entry tables and, before the pass, for the per-thread sample maxima.
-constexpr int kRingBytes = kWaves * kRing * 40;
+constexpr int kHitList = 192;   // positions a wave can collect in one expansion (a ring holds kRing * 16 elements)
+constexpr int kRingBytes = kWaves * (kRing * 40 + kHitList * 2);
 static_assert(kRingBytes >= 3 * 256 * 4, "ring space must hold the sort tables");
 inline size_t truncate_lds_bytes(int lds_recs) { return size_t(kRingBytes) + size_t(8) * lds_recs; }
+inline int truncate_sort_scratch(int k_sel) { return k_sel + k_sel / 2 + 64; }   // records the sort may need
 
 struct TruncateShared {
   BlockScratch red;
@@ -170,8 +174,8 @@ __device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uin
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, float k2, uint64_t* cand, int cap,
-                               int lds_recs, uint32_t* tables, TruncateShared& sh, bool need_sum, float& c_ref,
-                               double& z_c, int& st) {
+                               uint64_t* sort_tmp, int sort_tmp_cap, uint32_t* tables, TruncateShared& sh,
+                               bool need_sum, float& c_ref, double& z_c, int& st) {
   constexpr int E = ElemTraits<T>::kPerVec;
   const int tid = threadIdx.x;
   const int n_edge = rs.head + rs.tail;
@@ -226,8 +230,8 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
   const int n_groups = sh.cand_count;
   float tau = -INFINITY;                               // fewer than k_eff non-empty groups: take everything
   if (n_groups >= k_eff) {
-    if (!bucket_sort_desc(cand, n_groups, cand + n_groups, lds_recs - n_groups, cand, k_eff, tables, tables + 256,
-                          tables + 512, sh.red))
+    if (!bucket_sort_desc(cand, n_groups, sort_tmp, sort_tmp_cap, cand, k_eff, tables, tables + 256, tables + 512,
+                          sh.red))
       return -1;
     tau = cand_value(cand[k_eff - 1]);
   }
@@ -278,34 +282,54 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
 // index (in vectors, within the row's aligned body) of each.
 struct RingPair { uint4 w[2]; };
 
-// Expands the hit pairs parked in a wave's ring into candidate records (elements above tau0).
+// Expands the hit pairs parked in a wave's ring into candidate records (elements above tau0).  The
+// n pairs are n * 2E consecutive elements in LDS.  Stage 1 sweeps them 64 at a time, one element per
+// lane, and packs the positions of the elements above tau0 into a per-wave list; stage 2 turns that
+// dense list into records, one per lane, after a single reservation in the shared candidate array.
+template <typename T> __device__ __forceinline__ float ring_elem(const unsigned char* ring, uint32_t g);
+template <> __device__ __forceinline__ float ring_elem<float>(const unsigned char* ring, uint32_t g) {
+  return reinterpret_cast<const float*>(ring)[g];
+}
+template <> __device__ __forceinline__ float ring_elem<Bf16>(const unsigned char* ring, uint32_t g) {
+  return as_f32(uint32_t(reinterpret_cast<const uint16_t*>(ring)[g]) << 16);
+}
+
 template <typename T>
-__device__ __forceinline__ void expand_ring(const RingPair* ring, const uint2* ring_vidx, int n, float tau0,
-                                            uint32_t head, uint64_t* cand, int cap, TruncateShared& sh) {
+__device__ __forceinline__ void expand_ring(const RingPair* ring, const uint2* ring_vidx, uint16_t* hitlist, int n,
+                                            float tau0, uint32_t head, uint64_t* cand, int cap, TruncateShared& sh,
+                                            int& lost) {
   constexpr int E = ElemTraits<T>::kPerVec;
-  const int lane = lane_id();
-  if (lane < n) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      float v[E];
-      unpack<T>(ring[lane].w[h], v);
-      const uint32_t base = head + (h == 0 ? ring_vidx[lane].x : ring_vidx[lane].y) * E;
-#pragma unroll
-      for (int e = 0; e < E; ++e) {
-        if (v[e] > tau0) {
-          const int pos = atomicAdd(&sh.cand_count, 1);
-          if (pos < cap) cand[pos] = make_cand(v[e], base + e);
-        }
-      }
+  const unsigned char* bytes = reinterpret_cast<const unsigned char*>(ring);
+  const uint32_t lane = uint32_t(lane_id());
+  const uint32_t total = uint32_t(n) * 2 * E;
+  int hcnt = 0;
+  for (uint32_t g0 = 0; g0 < total; g0 += 64) {
+    const uint32_t g = g0 + lane;
+    const bool hit = g < total && ring_elem<T>(bytes, g) > tau0;
+    const uint64_t mask = ballot(hit);
+    if (mask != 0) {
+      const int pos = hcnt + lanes_below(mask);
+      if (hit && pos < kHitList) hitlist[pos] = uint16_t(g);
+      hcnt += __popcll(mask);
+    }
+  }
+  if (hcnt > kHitList) { lost = 1; hcnt = kHitList; }
+  if (hcnt == 0) return;
+  int base = 0;
+  if (lane == 0) base = atomicAdd(&sh.cand_count, hcnt);
+  base = __builtin_amdgcn_readfirstlane(base);
+  for (int h0 = 0; h0 < hcnt; h0 += 64) {
+    const int h = h0 + int(lane);
+    if (h < hcnt && base + h < cap) {
+      const uint32_t g = hitlist[h];
+      const uint32_t slot = g / (2 * E), j = g % (2 * E);
+      const uint2 vi = ring_vidx[slot];
+      const uint32_t idx = head + (j < E ? vi.x : vi.y) * E + (j % E);
+      cand[base + h] = make_cand(ring_elem<T>(bytes, g), idx);
     }
   }
 }
 
-__device__ __forceinline__ float max3f(float a, float b, float c) {
-  float r;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-  return r;
-}
 template <typename T> __device__ __forceinline__ float vec_max(const float (&v)[ElemTraits<T>::kPerVec]);
 template <> __device__ __forceinline__ float vec_max<float>(const float (&v)[4]) {
   return max3f(max3f(v[0], v[1], v[2]), v[3], v[3]);
@@ -322,8 +346,13 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
   __shared__ TruncateShared sh;
   RingPair* ring_all = reinterpret_cast<RingPair*>(dyn_lds);
   uint2* ring_vidx_all = reinterpret_cast<uint2*>(dyn_lds + kWaves * kRing * 32);
+  uint16_t* hitlist_all = reinterpret_cast<uint16_t*>(dyn_lds + kWaves * kRing * 40);
   uint32_t* tables = reinterpret_cast<uint32_t*>(dyn_lds);          // 3 x 256 entries, aliasing the rings
-  uint64_t* cand = reinterpret_cast<uint64_t*>(dyn_lds + kRingBytes);
+  uint64_t* cand = reinterpret_cast<uint64_t*>(dyn_lds + p.ring_bytes);
+  // sort scratch: what is left of the ring space behind the tables, or (if that is too small for the
+  // requested k) the records behind the candidate capacity
+  uint64_t* sort_tmp = p.tmp_in_ring ? reinterpret_cast<uint64_t*>(dyn_lds + 3 * 256 * 4) : cand + p.sort_cap;
+  const int sort_tmp_cap = p.tmp_in_ring ? (p.ring_bytes - 3 * 256 * 4) / 8 : p.lds_recs - p.sort_cap;
 
   const int tid = threadIdx.x;
   const int lane = lane_id();
@@ -401,6 +430,7 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
       int lost = 0;
       RingPair* ring = ring_all + wave * kRing;
       uint2* ring_vidx = ring_vidx_all + wave * kRing;
+      uint16_t* hitlist = hitlist_all + wave * kHitList;
       const uint32_t head = uint32_t(rs.head);
 
       // Two vectors at a time: their exp2 terms go to the partial sums; if any of their elements is
@@ -438,8 +468,8 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
             }
           }
           wave_cnt += __popcll(mask);
-          if (wave_cnt > kRing / 2) {                  // wave-uniform
-            expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh);
+          if (wave_cnt > kRing / 3) {                  // wave-uniform
+            expand_ring<T>(ring, ring_vidx, hitlist, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh, lost);
             wave_cnt = 0;
           }
         }
@@ -480,7 +510,7 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
         if (v1 < nvec) d[1] = load_vec_stream(&rs.body[v1]);
         process_pair(d[0], d[1], v0, v1);
       }
-      expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh);
+      expand_ring<T>(ring, ring_vidx, hitlist, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh, lost);
       if (lost) sh.overflow = 1;
       // edge elements (row not 16-byte aligned, or V not a whole number of vectors)
       if (tid < n_edge) {
@@ -503,20 +533,20 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
   if (!fast_ok) {
     st |= 256;
     const bool need_sum = !(z_c > 0.0 && z_c < INFINITY);
-    n_cand = two_pass_select<T>(row, rs, p.k_sel, p.k2, cand, p.sort_cap, p.lds_recs, tables, sh, need_sum, c_ref, z_c, st);
+    n_cand = two_pass_select<T>(row, rs, p.k_sel, p.k2, cand, p.sort_cap, sort_tmp, sort_tmp_cap, tables, sh, need_sum,
+                                c_ref, z_c, st);
     if (n_cand < 0) n_cand = exact_select<T>(row, p.V, p.k_sel, p.k2, cand, tables, sh, c_ref, z_c, st);
   }
 
   // ---- sort the candidates into canonical order ------------------------------------------------
   __syncthreads();
-  if (!bucket_sort_desc(cand, n_cand, cand + n_cand, p.lds_recs - n_cand, cand, p.k_sel, tables, tables + 256,
-                        tables + 512, sh.red)) {
+  if (!bucket_sort_desc(cand, n_cand, sort_tmp, sort_tmp_cap, cand, p.k_sel, tables, tables + 256, tables + 512,
+                        sh.red)) {
     // the bin at the k-th place is too crowded for the scratch space (a row full of ties): radix selection
     // delivers exactly k candidates, which always fit
     st |= 256;
     n_cand = exact_select<T>(row, p.V, p.k_sel, p.k2, cand, tables, sh, c_ref, z_c, st);
-    bucket_sort_desc(cand, n_cand, cand + n_cand, p.lds_recs - n_cand, cand, p.k_sel, tables, tables + 256, tables + 512,
-                     sh.red);
+    bucket_sort_desc(cand, n_cand, sort_tmp, sort_tmp_cap, cand, p.k_sel, tables, tables + 256, tables + 512, sh.red);
   }
   const int k_eff = n_cand < p.k_sel ? n_cand : p.k_sel;
 

@@ -61,20 +61,24 @@ size_t plan_truncate(tslt_dtype dt, int64_t V, tslt::TruncateParams& p) {
   const int jprime = int(std::ceil(jc + 2.0 * std::sqrt(j > jc ? j - jc : 0.0) + 1.0));
   p.tau_bits = dt == TSLT_BF16 ? 16 : 20;
   p.jprime = 0;
-  // candidate capacity: always room for the fallback's 1024 group maxima; the sort needs k_sel more
-  // records of scratch behind the candidates plus room for the bin that straddles the k-th place
+  // candidate capacity: always room for the fallback's 1024 group maxima and for 2 * k_sel records.
+  // The sort needs about 1.5 * k_sel records of scratch: the ring space behind the sort's tables if
+  // that is large enough, else extra records behind the candidates.
   const int min_cap = (4 * tslt::kBlock + 16 > 2 * p.k_sel) ? 4 * tslt::kBlock + 16 : 2 * p.k_sel;
-  const int scratch = p.k_sel + p.k_sel / 2 + 64;
+  const int scratch = tslt::truncate_sort_scratch(p.k_sel);
+  p.ring_bytes = tslt::kRingBytes;
+  p.tmp_in_ring = (tslt::kRingBytes - 3 * 256 * 4) / 8 >= scratch ? 1 : 0;
+  const int extra = p.tmp_in_ring ? 0 : scratch;
   p.sort_cap = min_cap;
-  p.lds_recs = min_cap + scratch;
+  p.lds_recs = min_cap + extra;
   if (jprime <= int(0.8 * G)) {
     const double j_eff = -G * std::log(1.0 - double(jprime) / G);
     int sort_cap = int((j_eff + 5.0 * std::sqrt(j_eff) + 4.0) / f) + 16;   // mean + 5 sigma of the hits
     if (sort_cap < min_cap) sort_cap = min_cap;
-    if (tslt::truncate_lds_bytes(sort_cap + scratch) + sizeof(tslt::TruncateShared) + 256 <= kMaxLds) {
+    if (tslt::truncate_lds_bytes(sort_cap + extra) + sizeof(tslt::TruncateShared) + 256 <= kMaxLds) {
       p.jprime = jprime;
       p.sort_cap = sort_cap;
-      p.lds_recs = sort_cap + scratch;
+      p.lds_recs = sort_cap + extra;
     }
   }
   return tslt::truncate_lds_bytes(p.lds_recs);

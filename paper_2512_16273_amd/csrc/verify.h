@@ -21,11 +21,13 @@
 
 namespace tslt {
 
-constexpr int kSegVecs = 8;                         // 16-byte vectors per thread in a kernel-B segment
+constexpr int kSegVecs = 4;                         // 16-byte vectors per thread in a kernel-B segment
 constexpr int kSegVecsTotal = kSegVecs * kBlock;    // vectors per segment
 
+constexpr int kSubChunks = kSegVecs * kWaves;       // runs of 64 consecutive vectors per segment
+
 struct SegResult {       // one segment (or edge piece) of the resampled row
-  double sum;            // sum of exp64(s - smax) over the piece
+  double sum;            // sum of exp(s - smax) over the piece
   float smax;            // largest scaled logit of the piece (-inf if empty)
   int bad;               // NaN or +inf seen
 };
@@ -51,6 +53,7 @@ struct VerifyParams {
   int32_t* flags;        // [B, gamma] 1 accepted, 0 rejected, 2 row unusable
   int32_t* row_status;   // [B, gamma]
   SegResult* segs;       // [B, n_pieces]
+  double* subs;          // [B, n_seg, kSubChunks] sums of exp(s - smax of the segment) per run of 64 vectors
   int n_seg;             // body segments per row (upper bound used for the layout)
   int n_seg_grid;        // workgroups of kernel B1 per sequence
 };
@@ -64,22 +67,25 @@ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 inline size_t verify_workspace_bytes(int64_t B, int64_t gamma, int64_t V, int k_cap) {
   (void)k_cap;
   const size_t n_pieces = size_t(verify_segments(V)) + 2;
-  return align256(size_t(B) * gamma * 4) * 2 + align256(size_t(B) * n_pieces * sizeof(SegResult));
+  return align256(size_t(B) * gamma * 4) * 2 + align256(size_t(B) * n_pieces * sizeof(SegResult)) +
+         align256(size_t(B) * verify_segments(V) * kSubChunks * sizeof(double));
 }
 inline void verify_carve_workspace(VerifyParams& p, void* ws) {
   char* w = reinterpret_cast<char*>(ws);
   p.flags = reinterpret_cast<int32_t*>(w); w += align256(size_t(p.B) * p.gamma * 4);
   p.row_status = reinterpret_cast<int32_t*>(w); w += align256(size_t(p.B) * p.gamma * 4);
-  p.segs = reinterpret_cast<SegResult*>(w);
   p.n_seg = verify_segments(p.V);
+  p.segs = reinterpret_cast<SegResult*>(w); w += align256(size_t(p.B) * (p.n_seg + 2) * sizeof(SegResult));
+  p.subs = reinterpret_cast<double*>(w);
 }
 
 struct VerifyShared {
   BlockScratch red;
   double bcast_d[4];
   int bcast_i[4];
-  double chunk_corr[64];
-  double thread_corr[kBlock];
+  double piece_val[kBlock];        // level 1: mass of every piece (n_pieces <= kBlock)
+  double sub_val[kSubChunks];      // level 2: mass of every run of 64 vectors of the chosen segment
+  double elem_corr[64 * 8];        // level 3: sparse correction per element of the chosen run
 };
 
 template <typename T> __device__ __forceinline__ const void* target_row(const VerifyParams& p, int64_t b, int j) {
@@ -263,7 +269,8 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
                                 const RowSplit& rs, int n_seg_row, int broken_flag) {
   constexpr int E = ElemTraits<T>::kPerVec;
   constexpr int kMaxPer = TSLT_MAX_K_CAP / kBlock;
-  constexpr int kChunk = kSegVecs * E;      // elements owned by one thread at level 2
+  constexpr int kRun = 64 * E;              // elements in a run of 64 vectors
+  constexpr int kPerT = kRun / kBlock;      // elements per thread at level 3
   const int tid = threadIdx.x;
   const int n_pieces = n_seg_row + 2;
   const SegResult* segs = p.segs + size_t(b) * (p.n_seg + 2);
@@ -288,7 +295,7 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
     double zp = 0.0;
     for (int k = tid; k < n_pieces; k += kBlock) {
       const double t = segs[k].smax > -INFINITY ? segs[k].sum * exp64(double(segs[k].smax) - double(smax)) : 0.0;
-      sh.thread_corr[k] = t;              // n_pieces <= kBlock (checked on the host)
+      sh.piece_val[k] = t;
       zp += t;
     }
     zp = block_sum_f64<kWaves>(zp, sh.red);
@@ -330,23 +337,25 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
     }
     sum_corr = block_sum_f64<kWaves>(sum_corr, sh.red);
     double total = zp + sum_corr;
+    bool use_corr = true;
     if (!(total > 0.0)) {          // defensive: an all-zero residual falls back to p itself
 #pragma unroll
       for (int k = 0; k < kMaxPer; ++k) corr[k] = 0.0;
       total = zp;
+      use_corr = false;
     }
     const double target = double(p.u_resample[b * (p.gamma + 1) + jstar]) * total;
 
     // ---- level 1: which piece ---------------------------------------------------------------------
 #pragma unroll
     for (int k = 0; k < kMaxPer; ++k)
-      if (yi[k] >= 0 && corr[k] != 0.0) atomicAdd(&sh.thread_corr[piece_of<T>(rs, n_seg_row, yi[k])], corr[k]);
+      if (yi[k] >= 0 && corr[k] != 0.0) atomicAdd(&sh.piece_val[piece_of<T>(rs, n_seg_row, yi[k])], corr[k]);
     __syncthreads();
     if (tid == 0) {
       double run = 0.0, before = 0.0, last_before = 0.0;
       int piece = -1, last_pos = -1;
       for (int k = 0; k < n_pieces; ++k) {
-        const double t = sh.thread_corr[k];
+        const double t = sh.piece_val[k];
         if (t > 0.0) {
           last_pos = k; last_before = run;
           if (run + t > target) { piece = k; before = run; break; }
@@ -366,7 +375,6 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
       // an edge piece: fewer than E elements, walked by one thread
       if (tid == 0) {
         const int e0 = piece == 0 ? 0 : rs.head, e1 = piece == 0 ? rs.head : rs.head + rs.tail;
-        const bool use_corr = total != zp || sum_corr == 0.0;
         double run = before_piece;
         for (int e = e0; e < e1; ++e) {
           const int64_t y = edge_index<T>(rs, e);
@@ -390,82 +398,87 @@ __device__ void resample_finish(const VerifyParams& p, VerifyShared& sh, int64_t
       __syncthreads();
       token = sh.bcast_i[3];
     } else if (piece > 0) {
-      // ---- level 2: which thread's chunk of kSegVecs consecutive vectors of the body segment ------
-      const int64_t v0 = int64_t(piece - 1) * kSegVecsTotal + int64_t(tid) * kSegVecs;
-      const int64_t seg_first_elem = rs.head + int64_t(piece - 1) * kSegVecsTotal * E;
-      sh.thread_corr[tid] = 0.0;
+      // ---- level 2: which run of 64 consecutive vectors of the body segment ------------------------
+      const int seg = piece - 1;
+      const int64_t seg_first_vec = int64_t(seg) * kSegVecsTotal;
+      const int64_t seg_first_elem = rs.head + seg_first_vec * E;
+      const double seg_scale = exp64(double(segs[piece].smax) - double(smax));
+      const double* subs = p.subs + (size_t(b) * p.n_seg + seg) * kSubChunks;
+      if (tid < kSubChunks) sh.sub_val[tid] = subs[tid] * seg_scale;
       __syncthreads();
 #pragma unroll
       for (int k = 0; k < kMaxPer; ++k)
         if (yi[k] >= 0 && corr[k] != 0.0 && piece_of<T>(rs, n_seg_row, yi[k]) == piece)
-          atomicAdd(&sh.thread_corr[(yi[k] - seg_first_elem) / kChunk], corr[k]);
+          atomicAdd(&sh.sub_val[(yi[k] - seg_first_elem) / kRun], corr[k]);
       __syncthreads();
-      double mine = 0.0;
-#pragma unroll
-      for (int i = 0; i < kSegVecs; ++i) {
-        if (v0 + i < rs.nvec) {
-          float v[E];
-          unpack<T>(load_vec(&rs.body[v0 + i]), v);
-#pragma unroll
-          for (int e = 0; e < E; ++e) mine += exp64(double(__fmul_rn(v[e], p.rT)) - double(smax));
+      if (tid == 0) {
+        double run = before_piece, before = before_piece, last_before = before_piece;
+        int sub = -1, last_pos = -1;
+        for (int c = 0; c < kSubChunks; ++c) {
+          const double t = sh.sub_val[c];
+          if (t > 0.0) {
+            last_pos = c; last_before = run;
+            if (run + t > target) { sub = c; before = run; break; }
+            run += t;
+          }
         }
+        if (sub < 0) { sub = last_pos; before = last_before; }
+        sh.bcast_i[1] = sub;
+        sh.bcast_d[1] = before;
       }
-      mine += sh.thread_corr[tid];
-      if (mine < 0.0) mine = 0.0;
-      double seg_total;
-      const double excl = block_excl_scan_f64<kWaves>(mine, sh.red, seg_total);
-      // the first thread whose inclusive prefix passes the target; else the last one with mass
-      int first_pass = (mine > 0.0 && before_piece + excl + mine > target) ? tid : 0x7FFFFFFF;
-      int last_mass = mine > 0.0 ? tid : -1;
-#pragma unroll
-      for (int m = 32; m > 0; m >>= 1) {
-        const int o = __shfl_xor(first_pass, m, 64); first_pass = o < first_pass ? o : first_pass;
-        const int q = __shfl_xor(last_mass, m, 64); last_mass = q > last_mass ? q : last_mass;
-      }
+      for (int i = tid; i < kRun; i += kBlock) sh.elem_corr[i] = 0.0;
       __syncthreads();
-      if (lane_id() == 0) { sh.red.i[wave_id()] = first_pass; sh.red.i[8 + wave_id()] = last_mass; }
-      __syncthreads();
-      first_pass = 0x7FFFFFFF; last_mass = -1;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        first_pass = sh.red.i[w] < first_pass ? sh.red.i[w] : first_pass;
-        last_mass = sh.red.i[8 + w] > last_mass ? sh.red.i[8 + w] : last_mass;
-      }
-      const int owner = first_pass != 0x7FFFFFFF ? first_pass : last_mass;
-      if (tid == owner) sh.bcast_d[1] = before_piece + excl;
-      if (tid < 64) sh.chunk_corr[tid] = 0.0;
-      __syncthreads();
-      if (owner >= 0) {
-        // ---- level 3: which element of the owner's chunk -----------------------------------------
-        const double before_chunk = sh.bcast_d[1];
-        const int64_t chunk_first = seg_first_elem + int64_t(owner) * kChunk;
+      const int sub = sh.bcast_i[1];
+      const double before_run = sh.bcast_d[1];
+      if (sub >= 0) {
+        // ---- level 3: which element of that run; thread t owns kPerT consecutive elements ------------
+        const int64_t run_first = seg_first_elem + int64_t(sub) * kRun;
 #pragma unroll
         for (int k = 0; k < kMaxPer; ++k)
-          if (yi[k] >= chunk_first && yi[k] < chunk_first + kChunk) sh.chunk_corr[yi[k] - chunk_first] = corr[k];
+          if (yi[k] >= run_first && yi[k] < run_first + kRun) sh.elem_corr[yi[k] - run_first] = corr[k];
         __syncthreads();
-        if (tid < 64) {
-          const int64_t y = chunk_first + tid;
-          double v = 0.0;
-          if (tid < kChunk && (y - rs.head) / E < rs.nvec) {
-            const float t = load_elem<T>(row, y);
-            if (t > -INFINITY) v = exp64(double(__fmul_rn(t, p.rT)) - double(smax));
-            v += sh.chunk_corr[tid];
-            if (v < 0.0) v = 0.0;
-          }
-          double inc = v;
+        double v[kPerT];
+        double mine = 0.0;
 #pragma unroll
-          for (int d = 1; d < 64; d <<= 1) {
-            const double up = shfl_up_f64(inc, d);
-            if (tid >= d) inc += up;
+        for (int q = 0; q < kPerT; ++q) {
+          const int64_t y = run_first + tid * kPerT + q;
+          v[q] = 0.0;
+          if ((y - rs.head) / E < rs.nvec) {
+            const float t = load_elem<T>(row, y);
+            v[q] = exp64(double(__fmul_rn(t, p.rT)) - double(smax)) + sh.elem_corr[tid * kPerT + q];
+            if (v[q] < 0.0) v[q] = 0.0;
           }
-          const uint64_t pm = ballot(v > 0.0 && before_chunk + inc > target), mm = ballot(v > 0.0);
-          int pick = -1;
-          if (pm) pick = __builtin_ctzll(pm);
-          else if (mm) pick = 63 - __builtin_clzll(mm);
-          if (tid == 0) sh.bcast_i[3] = pick >= 0 ? int(chunk_first + pick) : -1;
+          mine += v[q];
+        }
+        double run_total;
+        const double excl = block_excl_scan_f64<kWaves>(mine, sh.red, run_total);
+        // element at which the cumulative mass passes the target, else the last one with mass
+        int first_pass = 0x7FFFFFFF, last_mass = -1;
+        double run = before_run + excl;
+#pragma unroll
+        for (int q = 0; q < kPerT; ++q) {
+          if (v[q] > 0.0) {
+            run += v[q];
+            last_mass = tid * kPerT + q;
+            if (run > target && first_pass == 0x7FFFFFFF) first_pass = tid * kPerT + q;
+          }
+        }
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) {
+          const int o = __shfl_xor(first_pass, m, 64); first_pass = o < first_pass ? o : first_pass;
+          const int q = __shfl_xor(last_mass, m, 64); last_mass = q > last_mass ? q : last_mass;
         }
         __syncthreads();
-        token = sh.bcast_i[3];
+        if (lane_id() == 0) { sh.red.i[wave_id()] = first_pass; sh.red.i[8 + wave_id()] = last_mass; }
+        __syncthreads();
+        first_pass = 0x7FFFFFFF; last_mass = -1;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+          first_pass = sh.red.i[w] < first_pass ? sh.red.i[w] : first_pass;
+          last_mass = sh.red.i[8 + w] > last_mass ? sh.red.i[8 + w] : last_mass;
+        }
+        const int pick = first_pass != 0x7FFFFFFF ? first_pass : last_mass;
+        token = pick >= 0 ? int(run_first + pick) : -1;
       }
     }
   }
@@ -519,7 +532,7 @@ __global__ __launch_bounds__(kBlock) void verify_sweep_kernel(const VerifyParams
   SegResult* segs = p.segs + size_t(b) * (p.n_seg + 2);
 
   if (!broken && seg < n_seg_row) {
-    // ---- this workgroup's segment, held in registers: maximum first, then the fp64 sum -----------
+    // ---- this workgroup's segment, held in registers: maximum first, then the fp64 sums
     uint4 d[kSegVecs];
     const int64_t vbase = int64_t(seg) * kSegVecsTotal;
 #pragma unroll
@@ -528,39 +541,55 @@ __global__ __launch_bounds__(kBlock) void verify_sweep_kernel(const VerifyParams
       d[i] = neg_inf_vec<T>();
       if (vi < rs.nvec) d[i] = load_vec(&rs.body[vi]);
     }
+    // this segment's own maximum is the reference of its sums; a row that kernel A has accepted or
+    // rejected has been validated there, the bonus row is checked here
     float vmax = -INFINITY;
     int bad = 0;
+    const bool check = jstar == p.gamma;
 #pragma unroll
     for (int i = 0; i < kSegVecs; ++i) {
       float v[E];
       unpack<T>(d[i], v);
+      if (check) {
 #pragma unroll
-      for (int e = 0; e < E; ++e) {
-        bad |= (v[e] != v[e] || v[e] == INFINITY) ? 1 : 0;
-        vmax = fmaxf(vmax, v[e]);
+        for (int e = 0; e < E; ++e) bad |= (v[e] != v[e] || v[e] == INFINITY) ? 1 : 0;
       }
+#pragma unroll
+      for (int e = 0; e < E; e += 2) vmax = max3f(vmax, v[e], v[e + 1]);
     }
     vmax = block_max_f32<kWaves>(vmax, sh.red);
     bad = __syncthreads_or(bad);
     const float smax = __fmul_rn(vmax, p.rT);      // scaling is monotone: the largest s is at the largest t
+    double* subs = p.subs + (size_t(b) * p.n_seg + seg) * kSubChunks;
     double sum = 0.0;
     if (smax > -INFINITY && !bad) {
       const double m = double(smax);
-      double s0 = 0.0, s1 = 0.0;
 #pragma unroll
       for (int i = 0; i < kSegVecs; ++i) {
         float v[E];
         unpack<T>(d[i], v);
+        double s0 = 0.0, s1 = 0.0;
 #pragma unroll
         for (int e = 0; e < E; e += 2) {            // -inf gives exactly 0
           s0 += exp64(double(__fmul_rn(v[e], p.rT)) - m);
           s1 += exp64(double(__fmul_rn(v[e + 1], p.rT)) - m);
         }
+        const double run_sum = wave_sum_f64(s0 + s1);   // run (i, wave): 64 consecutive vectors
+        if (lane_id() == 0) subs[i * kWaves + wave_id()] = run_sum;
+        sum += run_sum;
       }
-      sum = s0 + s1;
+    } else if (tid < kSubChunks) {
+      subs[tid] = 0.0;
     }
-    sum = block_sum_f64<kWaves>(sum, sh.red);
-    if (tid == 0) { segs[1 + seg].sum = sum; segs[1 + seg].smax = smax; segs[1 + seg].bad = bad; }
+    // every lane of a wave holds its wave's total
+    __syncthreads();
+    if (lane_id() == 0) sh.red.d[wave_id()] = sum;
+    __syncthreads();
+    if (tid == 0) {
+      double t = 0.0;
+      for (int w = 0; w < kWaves; ++w) t += sh.red.d[w];
+      segs[1 + seg].sum = t; segs[1 + seg].smax = smax; segs[1 + seg].bad = bad;
+    }
   }
   if (!broken && seg == 0 && tid == 0) {
     // the two edge pieces (at most E-1 elements each)

@@ -1,0 +1,80 @@
+"""Host-side checks that need no GPU: the C-ABI library exports what include/tslt.h declares, argument
+errors are reported before anything is launched, and the fp64 exp used by the inverse-CDF kernels is
+accurate (its header compiles for the host too)."""
+import ctypes
+import os
+import re
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2512_16273_amd", "libtslt.so")
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tslt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tslt_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2512_16273_amd import build
+        build.build_library(verbose=False)
+    return ctypes.CDLL(LIB)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_symbols()
+    assert {"tslt_truncate", "tslt_sample", "tslt_verify", "tslt_verify_tree"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2512_16273_amd import tslt
+    assert set(tslt.EXPORTS) == set(names)
+
+
+def test_workspace_sizes_and_version(lib):
+    lib.tslt_workspace_bytes.restype = ctypes.c_size_t
+    lib.tslt_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32]
+    assert lib.tslt_version() >= 100
+    assert lib.tslt_workspace_bytes(0, 2048, 0, 128256, 256) == 0          # truncate needs none
+    small = lib.tslt_workspace_bytes(2, 16, 8, 32000, 64)
+    big = lib.tslt_workspace_bytes(2, 256, 8, 128256, 256)
+    assert 0 < small < big < 64 << 20 and big % 256 == 0
+    assert lib.tslt_workspace_bytes(2, 0, 8, 32000, 64) == 0
+
+
+def test_argument_errors_are_found_on_the_host(lib):
+    """Bad arguments return a negative code and a message; nothing touches the (absent) GPU."""
+    lib.tslt_last_error.restype = ctypes.c_char_p
+    vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    lib.tslt_truncate.restype = ctypes.c_int
+    lib.tslt_truncate.argtypes = [vp, ctypes.c_int, i64, i64, i64, f32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    fake = ctypes.c_void_p(0x1000)
+    def call(dt=1, rows=4, V=1000, stride=1000, T=1.0, k=4, p=0.0, cap=4, ptr=fake):
+        return lib.tslt_truncate(ptr, dt, rows, V, stride, T, k, p, cap, fake, fake, None, fake, None, None, None, 0, None)
+    assert call(T=0.0) == -1 and b"temperature" in lib.tslt_last_error()
+    assert call(dt=7) == -1
+    assert call(stride=10) == -1
+    assert call(cap=0) == -2 and call(cap=5000) == -2
+    assert call(k=-1) == -1
+    assert call(ptr=None) == -1
+    assert call(ptr=ctypes.c_void_p(0x1001)) == -1                          # bf16 row at an odd address
+    assert call(rows=0) == 0                                                 # empty batch: nothing to do
+    lib.tslt_sample.restype = ctypes.c_int
+    lib.tslt_sample.argtypes = [vp, vp, vp, i64, i32, vp, i32, i32, vp, vp, vp]
+    assert lib.tslt_sample(fake, fake, fake, 4, 2048, fake, 1, 0, fake, None, None) == -2
+    assert lib.tslt_sample(None, fake, fake, 4, 16, fake, 1, 0, fake, None, None) == -1
+
+
+def test_exp64_header_matches_libm(tmp_path):
+    """The kernels' fp64 exp, compiled for the host, against libm's long-double exp."""
+    exe = tmp_path / "exp64_check"
+    subprocess.run(["g++", "-O2", "-ffp-contract=off", "-mfma", "-I", os.path.join(ROOT, "paper_2512_16273_amd", "csrc"),
+                    "-o", str(exe), os.path.join(ROOT, "tests", "exp64_check.cpp")], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    m = re.search(r"max_ulp ([0-9.]+) edge (\d)", out)
+    assert m and float(m.group(1)) < 1.5 and m.group(2) == "1", out
