@@ -60,7 +60,13 @@ enum {
   TSLT_ROW_EXACT_PATH = 256      /* informational: the row took the multi-pass selection path */
 };
 
-enum { TSLT_OP_TRUNCATE = 0, TSLT_OP_SAMPLE = 1, TSLT_OP_VERIFY = 2, TSLT_OP_VERIFY_TREE = 3 };
+enum {
+  TSLT_OP_TRUNCATE = 0,
+  TSLT_OP_SAMPLE = 1,
+  TSLT_OP_VERIFY = 2,
+  TSLT_OP_VERIFY_TREE = 3,      /* tslt_verify_tree with node outputs: every node is evaluated */
+  TSLT_OP_VERIFY_TREE_PATH = 4  /* tslt_verify_tree without node outputs: only the verified path is sampled */
+};
 
 #define TSLT_MAX_K_CAP 1024   /* largest width of a sparse set */
 #define TSLT_MAX_TREE_DEPTH 16
@@ -183,8 +189,10 @@ int tslt_verify_resample(const void* target_logits, tslt_dtype dt, int64_t B, in
  *   out_len       [B] int32 length of that sequence, 1..depth+1
  *   out_ratio     [B, N_nodes-1] fp32 p^(i)/q_hat of every candidate that was tested (NaN if an
  *                 earlier sibling was accepted first, -1 if not in the set); may be NULL
- *   status        [B] int32; may be NULL
- * Workspace: tslt_workspace_bytes(TSLT_OP_VERIFY_TREE, B, N_nodes, V, k_cap).
+ *   status        [B] int32 TSLT_ROW_* bits of the nodes that were evaluated (every non-leaf node, and
+ *                 every leaf or only the leaf on the path, see out_node_token); may be NULL
+ * Workspace: tslt_workspace_bytes(TSLT_OP_VERIFY_TREE, B, N_nodes, V, k_cap) when node outputs are
+ * requested, tslt_workspace_bytes(TSLT_OP_VERIFY_TREE_PATH, ...) (much smaller) when both are NULL.
  */
 int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_t V, int64_t row_stride,
                      float target_temperature, int32_t depth, const int32_t* expansion,

@@ -328,8 +328,9 @@ def mcveri(p, q_idx, q_prob, cands, u_accept, u_resample) -> dict:
     P^(1) = P; candidate i is accepted iff u_i < min(1, p^(i)(x_i)/q_hat(x_i)); otherwise
     p^(i+1) = norm(max(0, p^(i) - q_hat)) with the same q_hat at every step; after k rejections
     the output is a sample of P^(k+1).  Returns token, slot (accepted candidate number or -1),
-    ratios, accept margins, the cdf margin and the stage acceptance rates beta^(i) =
-    sum_x min(q_hat, p^(i)) met on the way."""
+    ratios, accept margins, the cdf margin, the stage acceptance rates beta^(i) =
+    sum_x min(q_hat, p^(i)) met on the way, and per candidate the factor prod_{j<i} 1/Z_j by which an
+    error in p is magnified in p^(i) (Z_j = sum_x max(0, p^(j) - q_hat) <= 1 is the normaliser of update j)."""
     p_i = np.asarray(p, dtype=np.float64).copy()
     V = p_i.shape[0]
     ids = np.asarray(q_idx, dtype=np.int64)
@@ -337,12 +338,15 @@ def mcveri(p, q_idx, q_prob, cands, u_accept, u_resample) -> dict:
     k = len(cands)
     ratio = np.full(k, np.nan)
     margin = np.full(k, np.inf)
+    amp = np.ones(k)
+    gain = 1.0
     betas = []
     status = 0
     for i in range(k):
         x = int(cands[i])
         if x < 0:
             continue
+        amp[i] = gain
         betas.append(float(np.sum(np.minimum(q_dense, p_i))))
         if q_dense[x] <= 0.0:
             status |= STATUS_TOKEN_NOT_IN_SET
@@ -356,14 +360,15 @@ def mcveri(p, q_idx, q_prob, cands, u_accept, u_resample) -> dict:
             margin[i] = abs(ui - bound)
         if accepted:
             return dict(token=x, slot=i, ratio=ratio, accept_margin=margin, cdf_margin=np.inf,
-                        betas=betas, status=status)
+                        betas=betas, status=status, amp=amp)
         r = np.maximum(0.0, p_i - q_dense)
         Zr = np.sum(r)
         if Zr > 0.0:                        # always true after a rejection in exact arithmetic
             p_i = r / Zr
+            gain /= Zr
     y, mg = inverse_cdf(p_i, u_resample)
     return dict(token=y, slot=-1, ratio=ratio, accept_margin=margin, cdf_margin=mg, betas=betas,
-                status=status)
+                status=status, amp=amp)
 
 
 # ----------------------------------------------------------------------------------------------
@@ -402,6 +407,7 @@ def verify_tree_seq(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, 
     node_slot = np.full(n_nodes, -1, np.int32)
     ratio = np.full(max(n_nodes - 1, 0), np.nan)
     acc_margin = np.full(max(n_nodes - 1, 0), np.inf)
+    amp = np.ones(max(n_nodes - 1, 0))
     cdf_margin = np.full(n_nodes, np.inf)
     status = 0
     for n in range(n_nodes):
@@ -421,6 +427,7 @@ def verify_tree_seq(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, 
             node_token[n], node_slot[n] = r["token"], r["slot"]
             ratio[c0 - 1:c0 - 1 + k] = r["ratio"]
             acc_margin[c0 - 1:c0 - 1 + k] = r["accept_margin"]
+            amp[c0 - 1:c0 - 1 + k] = r["amp"]
             cdf_margin[n] = r["cdf_margin"]
             status |= r["status"]
         else:
@@ -438,7 +445,7 @@ def verify_tree_seq(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, 
         else:
             break
     return dict(node_token=node_token, node_slot=node_slot, seq=seq, len=length, path=path, ratio=ratio,
-                accept_margin=acc_margin, cdf_margin=cdf_margin, status=status)
+                accept_margin=acc_margin, amp=amp, cdf_margin=cdf_margin, status=status)
 
 
 def verify_tree(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, u_accept, u_resample) -> dict:
@@ -450,12 +457,12 @@ def verify_tree(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, u_ac
                node_slot=np.full((B, lay["n_nodes"]), -1, np.int32),
                seq=np.full((B, lay["depth"] + 1), -1, np.int32), len=np.zeros(B, np.int32),
                ratio=np.full((B, lay["n_nodes"] - 1), np.nan),
-               accept_margin=np.full((B, lay["n_nodes"] - 1), np.inf),
+               accept_margin=np.full((B, lay["n_nodes"] - 1), np.inf), amp=np.ones((B, lay["n_nodes"] - 1)),
                cdf_margin=np.full((B, lay["n_nodes"]), np.inf), status=np.zeros(B, np.int32), path=[])
     for b in range(B):
         r = verify_tree_seq(target[b], T, expansion, q_idx[b], q_logit[b], q_count[b], cand_tokens[b],
                             u_accept[b], u_resample[b])
-        for k in ("node_token", "node_slot", "seq", "ratio", "accept_margin", "cdf_margin"):
+        for k in ("node_token", "node_slot", "seq", "ratio", "accept_margin", "amp", "cdf_margin"):
             out[k][b] = r[k]
         out["len"][b] = r["len"]
         out["status"][b] = r["status"]

@@ -1,0 +1,557 @@
+// Row-level building blocks shared by chain and tree verification (Algorithms 3, 5 and 8):
+//   eval_row_on_set  one streaming pass over a target row for its softmax normaliser, then p and
+//                    q_hat at the indices of a received sparse set, in fp64;
+//   sweep_segment    fp64 sums of exp(s - s_max) over one segment of a row that has to be sampled;
+//   finish_core      combines a row's segment sums, applies the sparse corrections of the residual
+//                    distribution and finds, by inverse CDF, the token at which the cumulative mass
+//                    passes u * total.
+// fp64 is needed for the sampling: at V >= 128k the buckets of the inverse CDF are far narrower than
+// fp32 prefix sums can resolve.
+#pragma once
+#include "common.h"
+#include "exp64.h"
+
+namespace tslt {
+
+constexpr int kSegVecs = 4;                         // 16-byte vectors per thread in a sweep segment
+constexpr int kSegVecsTotal = kSegVecs * kBlock;    // vectors per segment
+constexpr int kSubChunks = kSegVecs * kWaves;       // runs of 64 consecutive vectors per segment
+constexpr int kSetPer = 1024 / kBlock;              // set entries per thread (TSLT_MAX_K_CAP / kBlock)
+
+struct SegResult {       // one segment (or edge piece) of a row that is being sampled
+  double sum;            // sum of exp(s - smax) over the piece
+  float smax;            // largest scaled logit of the piece (-inf if empty)
+  int bad;               // NaN or +inf seen
+};
+
+inline int row_segments(int64_t V) {
+  // body vectors are at most V / 4 (fp32); one more segment covers a ragged end
+  const int64_t nvec_max = V / 4 + 1;
+  return int((nvec_max + kSegVecsTotal - 1) / kSegVecsTotal);
+}
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+struct VerifyShared {
+  BlockScratch red;
+  double bcast_d[4];
+  int bcast_i[4];
+  double piece_val[kBlock];        // level 1: mass of every piece (n_pieces <= kBlock)
+  double sub_val[kSubChunks];      // level 2: mass of every run of 64 vectors of the chosen segment
+  double elem_corr[64 * 8];        // level 3: sparse correction per element of the chosen run
+};
+
+// ---------------------------------------------------------------------------------------------
+// One pass over a target row: partial sums of exp2(t*k2 - c), c referenced to the largest target
+// logit found at the set's indices; then, in fp64 over the <= 1024 received entries, p at those
+// indices (the set's fp32 terms are replaced by fp64 ones in the normaliser) and q_hat = softmax of
+// the received values.  Entry i of the set is held by thread i % 256, slot i / 256.
+//   p_s, q_s  target and draft probability of the entry (0 where the entry is unused)
+//   yi        token index of the entry, -1 if unused or out of range
+//   p_out     target mass outside the set
+//   ok / st   false with TSLT_ROW_* bits when the row is unusable (NaN, +inf, nothing above -inf)
+// ---------------------------------------------------------------------------------------------
+// log2 of a softmax term relative to the reference c: one fma with k2 = fl32(log2(e) / T).  (The
+// definition rounds s = t / T to fp32 first; not doing so here moves a term by at most 2^-24 of its
+// exponent, a few 1e-8 of the normaliser after the set's own terms have been replaced by fp64 ones.)
+__device__ __forceinline__ float scaled_arg(float v, float k2, float neg_c) { return __builtin_fmaf(v, k2, neg_c); }
+
+template <typename T>
+__device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit& rs, int64_t V, float rT, float k2,
+                                                const int32_t* qi, const float* ql, int count, VerifyShared& sh,
+                                                double (&p_s)[kSetPer], double (&q_s)[kSetPer], int (&yi)[kSetPer],
+                                                double& p_out, bool& ok, int& st) {
+  constexpr int E = ElemTraits<T>::kPerVec;
+  const int tid = threadIdx.x;
+  const int n_edge = rs.head + rs.tail;
+  const int64_t n_tiles = (rs.nvec + kBlock - 1) / kBlock;
+  float tv[kSetPer];       // raw target logit at entry
+  float gmax = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < kSetPer; ++k) {
+    const int i = tid + k * kBlock;
+    tv[k] = -INFINITY; yi[k] = -1;
+    if (i < count) {
+      const int y = qi[i];
+      if (y >= 0 && y < V) { yi[k] = y; tv[k] = load_elem<T>(row, y); }
+      gmax = fmaxf(gmax, tv[k]);
+    }
+  }
+  float vref = block_max_f32<kWaves>(gmax, sh.red);
+  if (!(vref > -INFINITY && vref < INFINITY)) {
+    // no usable reference in the set: take the start of the row
+    float m0 = -INFINITY;
+    for (int64_t i = tid; i < V && i < 4096; i += kBlock) m0 = fmaxf(m0, load_elem<T>(row, i));
+    vref = block_max_f32<kWaves>(m0, sh.red);
+  }
+  st = 0;
+  double z_c = 0.0;
+  float c_ref = __fmul_rn(vref, k2);
+  ok = vref > -INFINITY && vref < INFINITY;
+  if (ok) {
+    const float neg_c = -c_ref;
+    // fp32 sums only within a batch of U vectors: a long-lived fp32 accumulator that has met one large
+    // term rounds away the many small ones that follow, always downwards
+    double dacc = 0.0;
+    constexpr int U = 4;
+    for (int64_t t0 = 0; t0 < n_tiles; t0 += U) {
+      uint4 d[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t vi = (t0 + u) * kBlock + tid;
+        d[u] = neg_inf_vec<T>();
+        if (vi < rs.nvec) d[u] = load_vec_stream(&rs.body[vi]);
+      }
+      float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float v[E];
+        unpack<T>(d[u], v);
+#pragma unroll
+        for (int e = 0; e < E; e += 4) {
+          acc0 += fast_exp2(scaled_arg(v[e + 0], k2, neg_c));
+          acc1 += fast_exp2(scaled_arg(v[e + 1], k2, neg_c));
+          acc2 += fast_exp2(scaled_arg(v[e + 2], k2, neg_c));
+          acc3 += fast_exp2(scaled_arg(v[e + 3], k2, neg_c));
+        }
+      }
+      dacc += double((acc0 + acc1) + (acc2 + acc3));
+    }
+    if (tid < n_edge) dacc += double(fast_exp2(scaled_arg(load_elem<T>(row, edge_index<T>(rs, tid)), k2, neg_c)));
+    z_c = block_sum_f64<kWaves>(dacc, sh.red);
+    ok = z_c > 0.0 && z_c < INFINITY;
+  }
+  if (!ok) {
+    // exact redo: validity and true maximum first, then the sum referenced to it
+    int bad = 0, fin = 0;
+    float vmax = -INFINITY;
+    for (int64_t i = tid; i < V; i += kBlock) {
+      float v = load_elem<T>(row, i);
+      if (v != v || v == INFINITY) bad = 1;
+      else if (v > -INFINITY) { fin = 1; vmax = fmaxf(vmax, v); }
+    }
+    bad = block_sum_i32<kWaves>(bad, sh.red);
+    fin = block_sum_i32<kWaves>(fin, sh.red);
+    vmax = block_max_f32<kWaves>(vmax, sh.red);
+    if (bad) st |= 1;
+    else if (!fin) st |= 2;
+    else {
+      vref = vmax;
+      c_ref = __fmul_rn(vref, k2);
+      double acc = 0.0;
+      for (int64_t i = tid; i < V; i += kBlock) acc += double(fast_exp2(scaled_arg(load_elem<T>(row, i), k2, -c_ref)));
+      z_c = block_sum_f64<kWaves>(acc, sh.red);
+      ok = true;
+    }
+  }
+
+  // ---- fp64 over the set ----------------------------------------------------------------------
+  const float s_ref = __fmul_rn(vref, rT);
+  const double ql0 = count > 0 ? double(ql[0]) : 0.0;
+  double sum_e = 0.0, sum_t32 = 0.0, sum_w = 0.0;
+#pragma unroll
+  for (int k = 0; k < kSetPer; ++k) {
+    const int i = tid + k * kBlock;
+    p_s[k] = 0.0; q_s[k] = 0.0;
+    if (i < count) {
+      q_s[k] = exp64(double(ql[i]) - ql0);
+      sum_w += q_s[k];
+      if (yi[k] >= 0 && tv[k] > -INFINITY && ok) {
+        p_s[k] = exp64(double(__fmul_rn(tv[k], rT)) - double(s_ref));
+        sum_e += p_s[k];
+        sum_t32 += double(fast_exp2(scaled_arg(tv[k], k2, -c_ref)));
+      }
+    }
+  }
+  sum_e = block_sum_f64<kWaves>(sum_e, sh.red);
+  sum_t32 = block_sum_f64<kWaves>(sum_t32, sh.red);
+  sum_w = block_sum_f64<kWaves>(sum_w, sh.red);
+  double tail = z_c - sum_t32;
+  if (tail < 0.0) tail = 0.0;
+  tail *= exp2(double(c_ref) - double(vref) * double(k2));   // to the reference of the fp64 terms
+  const double Z = tail + sum_e;
+  p_out = ok ? tail / Z : 0.0;
+#pragma unroll
+  for (int k = 0; k < kSetPer; ++k) {
+    p_s[k] = ok ? p_s[k] / Z : 0.0;
+    q_s[k] = sum_w > 0.0 ? q_s[k] / sum_w : 0.0;
+  }
+}
+
+// Piece index (0 head edge, 1..n body segments, n+1 tail edge) that holds element y of the row.
+template <typename T> __device__ __forceinline__ int piece_of(const RowSplit& rs, int n_seg_row, int64_t y) {
+  constexpr int E = ElemTraits<T>::kPerVec;
+  if (y < rs.head) return 0;
+  const int64_t v = (y - rs.head) / E;
+  if (v >= rs.nvec) return n_seg_row + 1;
+  return 1 + int(v / kSegVecsTotal);
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp64 sweep of segment `seg` of a row (all 256 threads of a workgroup): segs[1 + seg] and the
+// kSubChunks run sums of the segment; the workgroup of segment 0 also does the two edge pieces.
+// `check` asks for NaN / +inf detection (rows that no earlier kernel has validated).
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void sweep_segment(const void* row, const RowSplit& rs, int seg, bool check, float rT,
+                                              SegResult* segs, double* subs, VerifyShared& sh) {
+  constexpr int E = ElemTraits<T>::kPerVec;
+  const int tid = threadIdx.x;
+  const int n_seg_row = int((rs.nvec + kSegVecsTotal - 1) / kSegVecsTotal);
+  if (seg < n_seg_row) {
+    // ---- this workgroup's segment, held in registers: maximum first, then the fp64 sums
+    uint4 d[kSegVecs];
+    const int64_t vbase = int64_t(seg) * kSegVecsTotal;
+#pragma unroll
+    for (int i = 0; i < kSegVecs; ++i) {
+      const int64_t vi = vbase + int64_t(i) * kBlock + tid;
+      d[i] = neg_inf_vec<T>();
+      if (vi < rs.nvec) d[i] = load_vec(&rs.body[vi]);
+    }
+    // this segment's own maximum is the reference of its sums
+    float vmax = -INFINITY;
+    int bad = 0;
+#pragma unroll
+    for (int i = 0; i < kSegVecs; ++i) {
+      float v[E];
+      unpack<T>(d[i], v);
+      if (check) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) bad |= (v[e] != v[e] || v[e] == INFINITY) ? 1 : 0;
+      }
+#pragma unroll
+      for (int e = 0; e < E; e += 2) vmax = max3f(vmax, v[e], v[e + 1]);
+    }
+    vmax = block_max_f32<kWaves>(vmax, sh.red);
+    bad = __syncthreads_or(bad);
+    const float smax = __fmul_rn(vmax, rT);      // scaling is monotone: the largest s is at the largest t
+    subs += size_t(seg) * kSubChunks;
+    double sum = 0.0;
+    if (smax > -INFINITY && !bad) {
+      const double m = double(smax);
+#pragma unroll
+      for (int i = 0; i < kSegVecs; ++i) {
+        float v[E];
+        unpack<T>(d[i], v);
+        double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+        for (int e = 0; e < E; e += 2) {            // -inf gives exactly 0
+          s0 += exp64(double(__fmul_rn(v[e], rT)) - m);
+          s1 += exp64(double(__fmul_rn(v[e + 1], rT)) - m);
+        }
+        const double run_sum = wave_sum_f64(s0 + s1);   // run (i, wave): 64 consecutive vectors
+        if (lane_id() == 0) subs[i * kWaves + wave_id()] = run_sum;
+        sum += run_sum;
+      }
+    } else if (tid < kSubChunks) {
+      subs[tid] = 0.0;
+    }
+    // every lane of a wave holds its wave's total
+    __syncthreads();
+    if (lane_id() == 0) sh.red.d[wave_id()] = sum;
+    __syncthreads();
+    if (tid == 0) {
+      double t = 0.0;
+      for (int w = 0; w < kWaves; ++w) t += sh.red.d[w];
+      segs[1 + seg].sum = t; segs[1 + seg].smax = smax; segs[1 + seg].bad = bad;
+    }
+  }
+  if (seg == 0 && tid == 0) {
+    // the two edge pieces (at most E-1 elements each)
+    for (int piece = 0; piece < 2; ++piece) {
+      const int e0 = piece == 0 ? 0 : rs.head, e1 = piece == 0 ? rs.head : rs.head + rs.tail;
+      float smax = -INFINITY;
+      int bad = 0;
+      for (int e = e0; e < e1; ++e) {
+        const float t = load_elem<T>(row, edge_index<T>(rs, e));
+        if (t != t || t == INFINITY) bad = 1;
+        smax = fmaxf(smax, __fmul_rn(t, rT));
+      }
+      double sum = 0.0;
+      if (smax > -INFINITY && !bad)
+        for (int e = e0; e < e1; ++e) {
+          const float t = load_elem<T>(row, edge_index<T>(rs, e));
+          if (t > -INFINITY) sum += exp64(double(__fmul_rn(t, rT)) - double(smax));
+        }
+      SegResult& o = segs[piece == 0 ? 0 : n_seg_row + 1];
+      o.sum = sum; o.smax = smax; o.bad = bad;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Inverse CDF of one row from its piece and run sums.
+// ---------------------------------------------------------------------------------------------
+struct FinishArgs {
+  const void* row;
+  RowSplit rs;
+  int n_seg_row;
+  int64_t V;
+  float rT;
+  const SegResult* segs;    // n_seg_row + 2 pieces of this row
+  const double* subs;       // [segment][kSubChunks] run sums of this row
+  const int32_t* qi;        // the sparse set whose residual is sampled (ignored when stages == 0)
+  const float* ql;
+  int count;
+  int stages;               // residual updates p <- norm(max(0, p - q_hat)) to apply; 0 samples p itself
+  float u;
+  int unusable;             // the row is known to be unusable: no token
+};
+
+// Returns the token (-1 if none) and ORs TSLT_ROW_* bits into st.  After m updates with the same q_hat
+// the distribution is c * p outside the set and a_i on it, where a and c follow the recursion
+// a <- max(0, a - q_hat) / Z, c <- c / Z, Z = sum(max(0, a - q_hat)) + c * p_out; in units of the row's
+// unnormalised terms e_y that is e_y outside the set and a_i * z_p / c on it.
+template <typename T>
+__device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st) {
+  constexpr int E = ElemTraits<T>::kPerVec;
+  constexpr int kMaxPer = kSetPer;
+  constexpr int kRun = 64 * E;              // elements in a run of 64 vectors
+  constexpr int kPerT = kRun / kBlock;      // elements per thread at level 3
+  const int tid = threadIdx.x;
+  const RowSplit& rs = a.rs;
+  const void* row = a.row;
+  const int n_seg_row = a.n_seg_row;
+  const int n_pieces = n_seg_row + 2;
+  const SegResult* segs = a.segs;
+  const int broken_flag = a.unusable;
+  const float rT = a.rT;
+  // maximum and validity of the row, from the pieces
+  float smax = -INFINITY;
+  int bad = 0;
+  if (!broken_flag)
+    for (int k = tid; k < n_pieces; k += kBlock) { smax = fmaxf(smax, segs[k].smax); bad |= segs[k].bad; }
+  smax = block_max_f32<kWaves>(smax, sh.red);
+  bad = __syncthreads_or(bad);
+  int token = -1;
+  const bool usable = !broken_flag && !bad && smax > -INFINITY;
+  if (!broken_flag && bad) st |= 1;
+  if (!broken_flag && !bad && !(smax > -INFINITY)) st |= 2;
+
+  if (usable) {
+    // unnormalised target mass of every piece, referenced to the row maximum, and their total z_p
+    double zp = 0.0;
+    for (int k = tid; k < n_pieces; k += kBlock) {
+      const double t = segs[k].smax > -INFINITY ? segs[k].sum * exp64(double(segs[k].smax) - double(smax)) : 0.0;
+      sh.piece_val[k] = t;
+      zp += t;
+    }
+    zp = block_sum_f64<kWaves>(zp, sh.red);
+
+    // sparse corrections at the set's indices: after `stages` residual updates the mass of entry i is
+    // a_i * z_p / c instead of e_i
+    const int stages = a.stages;
+    int count = stages > 0 ? a.count : 0;
+    const int32_t* qi = a.qi;
+    const float* ql = a.ql;
+    const double ql0 = count > 0 ? double(ql[0]) : 0.0;
+    double w64[kMaxPer], corr[kMaxPer], e_s[kMaxPer];
+    int yi[kMaxPer];
+    double sum_w = 0.0, sum_e = 0.0;
+#pragma unroll
+    for (int k = 0; k < kMaxPer; ++k) {
+      const int i = tid + k * kBlock;
+      w64[k] = 0.0; corr[k] = 0.0; e_s[k] = 0.0; yi[k] = -1;
+      if (i < count) {
+        w64[k] = exp64(double(ql[i]) - ql0);
+        sum_w += w64[k];
+        const int y = qi[i];
+        if (y >= 0 && y < a.V) {
+          yi[k] = y;
+          const float t = load_elem<T>(row, y);
+          e_s[k] = t > -INFINITY ? exp64(double(__fmul_rn(t, rT)) - double(smax)) : 0.0;
+          sum_e += e_s[k];
+        }
+      }
+    }
+    sum_w = block_sum_f64<kWaves>(sum_w, sh.red);
+    sum_e = block_sum_f64<kWaves>(sum_e, sh.red);
+    double sum_corr = 0.0;
+    if (count > 0) {
+      double av[kMaxPer];
+#pragma unroll
+      for (int k = 0; k < kMaxPer; ++k) { av[k] = e_s[k] / zp; w64[k] = w64[k] / sum_w; }
+      const double p_out = 1.0 - sum_e / zp;
+      double c = 1.0;
+      for (int sgi = 0; sgi < stages; ++sgi) {
+        double part = 0.0;
+#pragma unroll
+        for (int k = 0; k < kMaxPer; ++k) {
+          const double d = av[k] - w64[k];
+          av[k] = (yi[k] >= 0 && d > 0.0) ? d : 0.0;
+          part += av[k];
+        }
+        const double Zs = block_sum_f64<kWaves>(part, sh.red) + c * (p_out > 0.0 ? p_out : 0.0);
+        if (Zs > 0.0) {
+#pragma unroll
+          for (int k = 0; k < kMaxPer; ++k) av[k] /= Zs;
+          c /= Zs;
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < kMaxPer; ++k) {
+        if (yi[k] >= 0) {
+          corr[k] = av[k] * zp / c - e_s[k];
+          sum_corr += corr[k];
+        }
+      }
+    }
+    sum_corr = block_sum_f64<kWaves>(sum_corr, sh.red);
+    double total = zp + sum_corr;
+    bool use_corr = true;
+    if (!(total > 0.0)) {          // defensive: an all-zero residual falls back to p itself
+#pragma unroll
+      for (int k = 0; k < kMaxPer; ++k) corr[k] = 0.0;
+      total = zp;
+      use_corr = false;
+    }
+    const double target = double(a.u) * total;
+
+    // ---- level 1: which piece ---------------------------------------------------------------------
+#pragma unroll
+    for (int k = 0; k < kMaxPer; ++k)
+      if (yi[k] >= 0 && corr[k] != 0.0) atomicAdd(&sh.piece_val[piece_of<T>(rs, n_seg_row, yi[k])], corr[k]);
+    __syncthreads();
+    if (tid == 0) {
+      double run = 0.0, before = 0.0, last_before = 0.0;
+      int piece = -1, last_pos = -1;
+      for (int k = 0; k < n_pieces; ++k) {
+        const double t = sh.piece_val[k];
+        if (t > 0.0) {
+          last_pos = k; last_before = run;
+          if (run + t > target) { piece = k; before = run; break; }
+          run += t;
+        }
+      }
+      if (piece < 0) { piece = last_pos; before = last_before; }
+      sh.bcast_i[0] = piece;
+      sh.bcast_d[0] = before;
+    }
+    __syncthreads();
+    const int piece = sh.bcast_i[0];
+    const double before_piece = sh.bcast_d[0];
+    __syncthreads();
+
+    if (piece == 0 || piece == n_pieces - 1) {
+      // an edge piece: fewer than E elements, walked by one thread
+      {
+        const int e0 = piece == 0 ? 0 : rs.head;
+        if (tid < 2 * E) sh.elem_corr[tid] = 0.0;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kMaxPer; ++k)
+          if (yi[k] >= 0 && piece_of<T>(rs, n_seg_row, yi[k]) == piece) {
+            const int e = yi[k] < rs.head ? yi[k] : rs.head + int(yi[k] - (rs.head + rs.nvec * E));
+            sh.elem_corr[e - e0] = corr[k];
+          }
+        __syncthreads();
+      }
+      if (tid == 0) {
+        const int e0 = piece == 0 ? 0 : rs.head, e1 = piece == 0 ? rs.head : rs.head + rs.tail;
+        double run = before_piece;
+        for (int e = e0; e < e1; ++e) {
+          const int64_t y = edge_index<T>(rs, e);
+          const float t = load_elem<T>(row, y);
+          double v = t > -INFINITY ? exp64(double(__fmul_rn(t, rT)) - double(smax)) : 0.0;
+          if (use_corr) {
+            v += sh.elem_corr[e - e0];
+            if (v < 0.0) v = 0.0;
+          }
+          if (v > 0.0) {
+            token = int(y);
+            run += v;
+            if (run > target) break;
+          }
+        }
+        sh.bcast_i[3] = token;
+      }
+      __syncthreads();
+      token = sh.bcast_i[3];
+    } else if (piece > 0) {
+      // ---- level 2: which run of 64 consecutive vectors of the body segment ------------------------
+      const int seg = piece - 1;
+      const int64_t seg_first_vec = int64_t(seg) * kSegVecsTotal;
+      const int64_t seg_first_elem = rs.head + seg_first_vec * E;
+      const double seg_scale = exp64(double(segs[piece].smax) - double(smax));
+      const double* subs = a.subs + size_t(seg) * kSubChunks;
+      if (tid < kSubChunks) sh.sub_val[tid] = subs[tid] * seg_scale;
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < kMaxPer; ++k)
+        if (yi[k] >= 0 && corr[k] != 0.0 && piece_of<T>(rs, n_seg_row, yi[k]) == piece)
+          atomicAdd(&sh.sub_val[(yi[k] - seg_first_elem) / kRun], corr[k]);
+      __syncthreads();
+      if (tid == 0) {
+        double run = before_piece, before = before_piece, last_before = before_piece;
+        int sub = -1, last_pos = -1;
+        for (int c = 0; c < kSubChunks; ++c) {
+          const double t = sh.sub_val[c];
+          if (t > 0.0) {
+            last_pos = c; last_before = run;
+            if (run + t > target) { sub = c; before = run; break; }
+            run += t;
+          }
+        }
+        if (sub < 0) { sub = last_pos; before = last_before; }
+        sh.bcast_i[1] = sub;
+        sh.bcast_d[1] = before;
+      }
+      for (int i = tid; i < kRun; i += kBlock) sh.elem_corr[i] = 0.0;
+      __syncthreads();
+      const int sub = sh.bcast_i[1];
+      const double before_run = sh.bcast_d[1];
+      if (sub >= 0) {
+        // ---- level 3: which element of that run; thread t owns kPerT consecutive elements ------------
+        const int64_t run_first = seg_first_elem + int64_t(sub) * kRun;
+#pragma unroll
+        for (int k = 0; k < kMaxPer; ++k)
+          if (yi[k] >= run_first && yi[k] < run_first + kRun) sh.elem_corr[yi[k] - run_first] = corr[k];
+        __syncthreads();
+        double v[kPerT];
+        double mine = 0.0;
+#pragma unroll
+        for (int q = 0; q < kPerT; ++q) {
+          const int64_t y = run_first + tid * kPerT + q;
+          v[q] = 0.0;
+          if ((y - rs.head) / E < rs.nvec) {
+            const float t = load_elem<T>(row, y);
+            v[q] = exp64(double(__fmul_rn(t, rT)) - double(smax)) + sh.elem_corr[tid * kPerT + q];
+            if (v[q] < 0.0) v[q] = 0.0;
+          }
+          mine += v[q];
+        }
+        double run_total;
+        const double excl = block_excl_scan_f64<kWaves>(mine, sh.red, run_total);
+        // element at which the cumulative mass passes the target, else the last one with mass
+        int first_pass = 0x7FFFFFFF, last_mass = -1;
+        double run = before_run + excl;
+#pragma unroll
+        for (int q = 0; q < kPerT; ++q) {
+          if (v[q] > 0.0) {
+            run += v[q];
+            last_mass = tid * kPerT + q;
+            if (run > target && first_pass == 0x7FFFFFFF) first_pass = tid * kPerT + q;
+          }
+        }
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) {
+          const int o = __shfl_xor(first_pass, m, 64); first_pass = o < first_pass ? o : first_pass;
+          const int q = __shfl_xor(last_mass, m, 64); last_mass = q > last_mass ? q : last_mass;
+        }
+        __syncthreads();
+        if (lane_id() == 0) { sh.red.i[wave_id()] = first_pass; sh.red.i[8 + wave_id()] = last_mass; }
+        __syncthreads();
+        first_pass = 0x7FFFFFFF; last_mass = -1;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+          first_pass = sh.red.i[w] < first_pass ? sh.red.i[w] : first_pass;
+          last_mass = sh.red.i[8 + w] > last_mass ? sh.red.i[8 + w] : last_mass;
+        }
+        const int pick = first_pass != 0x7FFFFFFF ? first_pass : last_mass;
+        token = pick >= 0 ? int(run_first + pick) : -1;
+      }
+    }
+  }
+  return token;
+}
+
+}  // namespace tslt

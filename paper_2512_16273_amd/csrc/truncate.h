@@ -157,9 +157,9 @@ __device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uin
   }
   // the normaliser's fp32 partial sums, referenced to the true maximum
   c_ref = __fmul_rn(vmax, k2);
-  float acc = 0.0f;
-  for (int64_t i = tid; i < V; i += kBlock) acc += fast_exp2(__builtin_fmaf(load_elem<T>(row, i), k2, -c_ref));
-  z_c = block_sum_f64<kWaves>(double(acc), sh.red);
+  double acc = 0.0;
+  for (int64_t i = tid; i < V; i += kBlock) acc += double(fast_exp2(__builtin_fmaf(load_elem<T>(row, i), k2, -c_ref)));
+  z_c = block_sum_f64<kWaves>(acc, sh.red);
   __syncthreads();
   return k_eff;
 }
@@ -240,7 +240,7 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
   if (tid == 0) sh.cand_count = 0;
   __syncthreads();
   if (need_sum) c_ref = __fmul_rn(vmax, k2);
-  float acc = 0.f;
+  double acc = 0.0;
   for (int64_t t0 = 0; t0 < n_tiles; t0 += 4) {
     uint4 d[4];
 #pragma unroll
@@ -256,7 +256,7 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
       const uint32_t base = uint32_t(rs.head) + uint32_t((t0 + u) * kBlock + tid) * E;
 #pragma unroll
       for (int e = 0; e < E; ++e) {
-        if (need_sum) acc += fast_exp2(__builtin_fmaf(v[e], k2, -c_ref));
+        if (need_sum) acc += double(fast_exp2(__builtin_fmaf(v[e], k2, -c_ref)));
         if (v[e] >= tau && v[e] > -INFINITY) {
           const int pos = atomicAdd(&sh.cand_count, 1);
           if (pos < cap) cand[pos] = make_cand(v[e], base + e);
@@ -265,13 +265,13 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
     }
   }
   if (tid < n_edge) {
-    if (need_sum) acc += fast_exp2(__builtin_fmaf(edge_v, k2, -c_ref));
+    if (need_sum) acc += double(fast_exp2(__builtin_fmaf(edge_v, k2, -c_ref)));
     if (edge_v >= tau && edge_v > -INFINITY) {
       const int pos = atomicAdd(&sh.cand_count, 1);
       if (pos < cap) cand[pos] = make_cand(edge_v, uint32_t(edge_i));
     }
   }
-  if (need_sum) z_c = block_sum_f64<kWaves>(double(acc), sh.red);
+  if (need_sum) z_c = block_sum_f64<kWaves>(acc, sh.red);
   __syncthreads();
   const int n = sh.cand_count;
   __syncthreads();
@@ -425,7 +425,14 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
       // ---- the pass -------------------------------------------------------------------------
       const float neg_c = -c_ref;
       const float k2 = p.k2;
+      // fp32 sums live for one batch only and are then added to an fp64 total: a long-lived fp32
+      // accumulator that has met one large term rounds away the many small ones that follow
       float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+      double dacc = 0.0;
+      auto flush = [&]() {
+        dacc += double((acc0 + acc1) + (acc2 + acc3));
+        acc0 = acc1 = acc2 = acc3 = 0.f;
+      };
       int wave_cnt = 0;                                // pairs parked in this wave's ring
       int lost = 0;
       RingPair* ring = ring_all + wave * kRing;
@@ -480,6 +487,7 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
         const uint32_t t1 = s_stride, t2 = 2 * s_stride, t3 = 3 * s_stride;
         process_pair(d[0], d[1], tid, t1 * kBlock + tid);
         process_pair(d[2], d[3], t2 * kBlock + tid, t3 * kBlock + tid);
+        flush();
       }
       uint32_t first_generic_tile = kBatch;             // short rows: everything after the sample tiles
       if (long_row) {
@@ -498,6 +506,7 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
           const uint32_t v0 = b * (kBatch * kBlock) + tid;
           process_pair(d[0], d[1], v0, v0 + kBlock);
           process_pair(d[2], d[3], v0 + 2 * kBlock, v0 + 3 * kBlock);
+          flush();
         }
         first_generic_tile = n_full * kBatch;
       }
@@ -509,6 +518,7 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
         if (v0 < nvec) d[0] = load_vec_stream(&rs.body[v0]);
         if (v1 < nvec) d[1] = load_vec_stream(&rs.body[v1]);
         process_pair(d[0], d[1], v0, v1);
+        flush();
       }
       expand_ring<T>(ring, ring_vidx, hitlist, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh, lost);
       if (lost) sh.overflow = 1;
@@ -522,7 +532,8 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
           if (pos < p.sort_cap) cand[pos] = make_cand(edge_v, uint32_t(edge_i));
         }
       }
-      z_c = block_sum_f64<kWaves>(double(acc0) + double(acc1) + double(acc2) + double(acc3), sh.red);
+      flush();
+      z_c = block_sum_f64<kWaves>(dacc, sh.red);
       __syncthreads();
       n_cand = sh.cand_count;
       fast_ok = !sh.overflow && n_cand <= p.sort_cap && n_cand >= p.k_sel && z_c > 0.0 && z_c < INFINITY;

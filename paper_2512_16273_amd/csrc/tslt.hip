@@ -11,6 +11,7 @@
 #include "common.h"
 #include "sample.h"
 #include "truncate.h"
+#include "tree.h"
 #include "verify.h"
 
 namespace {
@@ -102,6 +103,10 @@ size_t tslt_workspace_bytes(int op, int64_t n_outer, int64_t n_inner, int64_t V,
   switch (op) {
     case TSLT_OP_VERIFY:
       return tslt::verify_workspace_bytes(n_outer, n_inner, V, k_cap);
+    case TSLT_OP_VERIFY_TREE:
+      return n_inner > 0 ? tslt::tree_workspace_bytes(n_outer, n_inner, V, true) : 0;
+    case TSLT_OP_VERIFY_TREE_PATH:
+      return n_inner > 0 ? tslt::tree_workspace_bytes(n_outer, n_inner, V, false) : 0;
     default:
       return 0;
   }
@@ -171,8 +176,8 @@ static int verify_impl(int phases, const char* name, const void* target_logits, 
   if (B < 0 || gamma < 1 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "%s: bad shape", name);
   if (V > 0x7FFFFFFF || B * (int64_t(gamma) + 1) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: sizes must fit 31 bits", name);
   if (gamma > 4096) return fail(TSLT_ERR_UNSUPPORTED, "%s: gamma > 4096", name);
-  if (tslt::verify_segments(V) + 2 > tslt::kBlock) return fail(TSLT_ERR_UNSUPPORTED, "%s: V too large", name);
-  if (B * int64_t(tslt::verify_segments(V)) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: B too large", name);
+  if (tslt::row_segments(V) + 2 > tslt::kBlock) return fail(TSLT_ERR_UNSUPPORTED, "%s: V too large", name);
+  if (B * int64_t(tslt::row_segments(V)) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: B too large", name);
   if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "%s: temperature must be > 0", name);
   if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "%s: k_cap must be in 1..%d", name, TSLT_MAX_K_CAP);
   if (B == 0) return TSLT_OK;
@@ -218,11 +223,54 @@ int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_
                      const float* u_accept, const float* u_resample, int32_t* out_node_token,
                      int32_t* out_node_slot, int32_t* out_seq, int32_t* out_len, float* out_ratio, int32_t* status,
                      void* ws, size_t ws_bytes, void* stream) {
-  (void)target_logits; (void)dt; (void)B; (void)V; (void)row_stride; (void)target_temperature; (void)depth;
-  (void)expansion; (void)q_idx; (void)q_logit; (void)q_count; (void)k_cap; (void)cand_tokens; (void)u_accept;
-  (void)u_resample; (void)out_node_token; (void)out_node_slot; (void)out_seq; (void)out_len; (void)out_ratio;
-  (void)status; (void)ws; (void)ws_bytes; (void)stream;
-  return fail(TSLT_ERR_UNSUPPORTED, "tslt_verify_tree: not built yet");
+  const char* name = "tslt_verify_tree";
+  if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "%s: unknown dtype %d", name, int(dt));
+  if (B < 0 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "%s: bad shape", name);
+  if (depth < 1 || !expansion) return fail(TSLT_ERR_INVALID_ARG, "%s: depth must be >= 1 and expansion given", name);
+  if (depth > TSLT_MAX_TREE_DEPTH) return fail(TSLT_ERR_UNSUPPORTED, "%s: depth > %d", name, TSLT_MAX_TREE_DEPTH);
+  if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "%s: temperature must be > 0", name);
+  if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "%s: k_cap must be in 1..%d", name, TSLT_MAX_K_CAP);
+  if (tslt::row_segments(V) + 2 > tslt::kBlock || V > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: V too large", name);
+  tslt::TreeParams p{};
+  int64_t width = 1, n_nodes = 1;
+  p.offsets[0] = 0;
+  for (int l = 0; l < depth; ++l) {
+    if (expansion[l] < 1 || expansion[l] > TSLT_MAX_BRANCH)
+      return fail(TSLT_ERR_UNSUPPORTED, "%s: expansion[%d] must be in 1..%d", name, l, TSLT_MAX_BRANCH);
+    p.expansion[l] = expansion[l];
+    p.offsets[l + 1] = int(n_nodes);
+    width *= expansion[l];
+    n_nodes += width;
+    if (n_nodes > (1 << 24)) return fail(TSLT_ERR_UNSUPPORTED, "%s: tree too large", name);
+  }
+  p.offsets[depth + 1] = int(n_nodes);
+  p.n_nodes = int(n_nodes);
+  p.n_int = int(n_nodes - width);
+  p.depth = depth;
+  const bool all_nodes = out_node_token != nullptr || out_node_slot != nullptr;
+  p.all_nodes = all_nodes ? 1 : 0;
+  p.tasks = all_nodes ? p.n_nodes : 1;
+  if (B * int64_t(p.tasks) * tslt::row_segments(V) > 0x7FFFFFFF || B * n_nodes > 0x7FFFFFFF)
+    return fail(TSLT_ERR_UNSUPPORTED, "%s: B * nodes too large", name);
+  if (B == 0) return TSLT_OK;
+  if (!target_logits || !q_idx || !q_logit || !q_count || !cand_tokens || !u_accept || !u_resample || !out_seq || !out_len)
+    return fail(TSLT_ERR_INVALID_ARG, "%s: null pointer", name);
+  if (reinterpret_cast<uintptr_t>(target_logits) % (dt == TSLT_BF16 ? 2 : 4)) return fail(TSLT_ERR_INVALID_ARG, "%s: logits not aligned to their element type", name);
+  const size_t need = tslt::tree_workspace_bytes(B, n_nodes, V, all_nodes);
+  if (!ws || ws_bytes < need || reinterpret_cast<uintptr_t>(ws) % 256)
+    return fail(TSLT_ERR_WORKSPACE, "%s: workspace of %zu bytes, 256-byte aligned, required", name, need);
+  p.target = target_logits; p.B = B; p.V = V; p.row_stride = row_stride;
+  p.rT = reciprocal_temperature(target_temperature);
+  p.k2 = log2e_over_T(p.rT);
+  p.q_idx = q_idx; p.q_logit = q_logit; p.q_count = q_count; p.k_cap = k_cap;
+  p.cand_tokens = cand_tokens; p.u_accept = u_accept; p.u_resample = u_resample;
+  p.out_node_token = out_node_token; p.out_node_slot = out_node_slot; p.out_seq = out_seq; p.out_len = out_len;
+  p.out_ratio = out_ratio; p.status = status;
+  tslt::tree_carve_workspace(p, ws);
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  hipError_t e = dt == TSLT_BF16 ? tslt::launch_verify_tree<tslt::Bf16>(p, s) : tslt::launch_verify_tree<float>(p, s);
+  if (e != hipSuccess) return hip_fail(e, name);
+  return TSLT_OK;
 }
 
 }  // extern "C"

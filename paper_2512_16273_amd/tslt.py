@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtslt.so")
 
 F32, BF16 = 0, 1
-OP_TRUNCATE, OP_SAMPLE, OP_VERIFY, OP_VERIFY_TREE = 0, 1, 2, 3
+OP_TRUNCATE, OP_SAMPLE, OP_VERIFY, OP_VERIFY_TREE, OP_VERIFY_TREE_PATH = 0, 1, 2, 3, 4
 ROW_NONFINITE, ROW_EMPTY, ROW_TOKEN_NOT_IN_SET, ROW_EXACT_PATH = 1, 2, 4, 256
 MAX_K_CAP = 1024
 
@@ -218,7 +218,7 @@ def verify_tree(target: torch.Tensor, temperature: float, expansion: Sequence[in
                "node_slot": torch.empty(B, n_nodes, dtype=torch.int32, device=dev) if all_nodes else None,
                "ratio": torch.empty(B, max(n_nodes - 1, 1), dtype=torch.float32, device=dev),
                "status": torch.empty(B, dtype=torch.int32, device=dev)}
-    need = workspace_bytes(OP_VERIFY_TREE, B, n_nodes, V, k_cap)
+    need = workspace_bytes(OP_VERIFY_TREE if all_nodes else OP_VERIFY_TREE_PATH, B, n_nodes, V, k_cap)
     ws = workspace if workspace is not None else _workspace(need, dev)
     exp_arr = (ctypes.c_int32 * depth)(*[int(k) for k in expansion])
     _check(lib.tslt_verify_tree(_ptr(target), _dtype_code(target), B, V, target.stride(1), float(temperature), depth,

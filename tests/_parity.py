@@ -93,3 +93,75 @@ def oracle_chain(draft_rows, target_rows, T, top_k, top_p, k_cap, u_sample, u_ac
     tokens = smp["token"].reshape(B, G)
     ver = O.verify_chain(target_rows, T, q_idx, q_logit, q_count, tokens, np.asarray(u_accept), np.asarray(u_resample))
     return dict(trunc=tr, tokens=tokens, q_idx=q_idx, q_logit=q_logit, q_count=q_count, verify=ver)
+
+
+def oracle_tree(draft_rows, target_rows, T, top_k, top_p, k_cap, expansion, u_sample, u_accept, u_resample,
+                without_replacement):
+    """The whole multi-candidate round on the host (Algorithms 7's sampling and 8): truncate every non-leaf
+    node's draft row, draw its k candidates, verify the tree.  draft_rows [B, N_int, V], target_rows
+    [B, N_nodes, V] fp32 numpy; u_sample [B, N_int, k_max]."""
+    B, n_int, V = draft_rows.shape
+    lay = O.tree_layout(expansion)
+    n_nodes = lay["n_nodes"]
+    tr = O.truncate(draft_rows.reshape(B * n_int, V), T, top_k, top_p, k_cap)
+    q_idx = tr["idx"].reshape(B, n_int, k_cap)
+    q_logit = tr["logit"].reshape(B, n_int, k_cap)
+    q_count = tr["count"].reshape(B, n_int)
+    cands = np.full((B, n_nodes - 1), -1, np.int32)
+    for b in range(B):
+        for n in range(n_int):
+            layer = int(np.searchsorted(lay["offsets"], n, side="right")) - 1
+            k = int(expansion[layer])
+            slots, _ = O.sample_row(q_logit[b, n], int(q_count[b, n]), np.asarray(u_sample)[b, n, :k], without_replacement)
+            c0 = O.child_node(lay, expansion, n, 0)
+            ok = slots >= 0
+            cands[b, c0 - 1:c0 - 1 + k][ok] = q_idx[b, n][slots[ok]]
+    ver = O.verify_tree(target_rows, T, expansion, q_idx, q_logit, q_count, cands, np.asarray(u_accept),
+                        np.asarray(u_resample))
+    return dict(trunc=tr, q_idx=q_idx, q_logit=q_logit, q_count=q_count, cands=cands, verify=ver, layout=lay)
+
+
+def compare_tree(gpu: dict, ref: dict, expansion, all_nodes=True, label=""):
+    """GPU tslt_verify_tree outputs against the oracle's.  A node whose acceptance tests include one within
+    1e-6 * amp of its boundary is left out, and so is the verified sequence of a tree whose path crosses
+    such a node; both are counted.  amp = prod_{j<i} 1/Z_j is the factor by which the i-th candidate's
+    ratio magnifies an error in p (each residual update divides by its normaliser Z_j < 1); it is 1 for
+    the first candidate, which is the single-candidate rule.  Ratios are compared to the same scale."""
+    v = ref["verify"]
+    lay = ref["layout"]
+    n_int, n_nodes = lay["n_internal"], lay["n_nodes"]
+    g = {k: to_np(x) for k, x in gpu.items() if x is not None}
+    B = v["seq"].shape[0]
+    near_nodes = near_seqs = 0
+    for b in range(B):
+        tag = f"{label} tree {b}"
+        risky = np.zeros(n_nodes, bool)
+        for n in range(n_int):
+            layer = int(np.searchsorted(lay["offsets"], n, side="right")) - 1
+            c0 = O.child_node(lay, expansion, n, 0)
+            sl = slice(c0 - 1, c0 - 1 + expansion[layer])
+            if np.any(v["accept_margin"][b, sl] < NEAR_TIE * v["amp"][b, sl]):
+                risky[n] = True
+        near_nodes += int(risky.sum())
+        if all_nodes:
+            okn = ~risky
+            assert np.array_equal(g["node_slot"][b][okn], v["node_slot"][b][okn]), tag
+            assert np.array_equal(g["node_token"][b][okn], v["node_token"][b][okn]), \
+                (tag, np.nonzero(g["node_token"][b] != v["node_token"][b])[0][:8])
+            assert (g["status"][b] & 7) == v["status"][b], (tag, g["status"][b], v["status"][b])
+        if any(risky[n] for n in v["path"][b]):
+            near_seqs += 1
+            continue
+        assert g["len"][b] == v["len"][b], (tag, g["len"][b], v["len"][b])
+        assert np.array_equal(g["seq"][b], v["seq"][b]), (tag, g["seq"][b], v["seq"][b])
+        if "ratio" in g:
+            tested = ~np.isnan(v["ratio"][b])
+            for n in range(n_int):
+                if risky[n]:
+                    layer = int(np.searchsorted(lay["offsets"], n, side="right")) - 1
+                    c0 = O.child_node(lay, expansion, n, 0)
+                    tested[c0 - 1:c0 - 1 + expansion[layer]] = False
+            err = np.abs(g["ratio"][b][tested] - v["ratio"][b][tested])
+            bound = RTOL * np.abs(v["ratio"][b][tested]) + NEAR_TIE * v["amp"][b][tested]
+            assert np.all(err <= bound), (tag, float(np.max(err / bound)))
+    return dict(trees=B, near_tie_nodes=near_nodes, near_tie_sequences=near_seqs)
