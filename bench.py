@@ -24,7 +24,8 @@ HBM_PEAK_GBS = 8000.0
 
 
 def algorithmic_bytes(w):
-    """Bytes the method has to move per step ("algorithmic bytes")."""
+    """Bytes the method has to move per step: every draft and target logit once, the sparse
+    representation once out and once in.  Re-reads (the resampled row) earn no credit."""
     s = 2 if w.dtype == "bf16" else 4
     rows_d, rows_t = w.B * w.gamma, w.B * (w.gamma + 1)
     draft = rows_d * w.V * s
@@ -44,32 +45,26 @@ def committed_traffic(kernel):
     return float(m.group(1)) if m else None
 
 
-def cpu_baseline(w, seed):
-    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
-    import numpy as np
-    import torch
+def cpu_baseline(w, host_set, budget_s=20.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload: whole
+    sequences of one of the timed input sets (copied to the host), as many as fit the time budget."""
     from oracle import tslt_oracle as O
-    from paper_2512_16273_amd import workloads as W
-    n_seq = 3
-    ws = W.scaled(w, B=n_seq)
-    c = W.make_chain(ws, seed, "cpu")
-    draft = c["draft"].float().numpy().reshape(n_seq * w.gamma, w.V)
-    target = c["target"].float().numpy()
+    draft, target = host_set["draft"], host_set["target"]
     t0 = time.perf_counter()
     done = 0
-    for b in range(n_seq):
-        rows = draft[b * w.gamma:(b + 1) * w.gamma]
+    for b in range(w.B):
+        rows = draft[b].float().numpy()
         tr = O.truncate(rows, w.T, w.top_k, w.top_p, w.k_cap)
-        smp = O.sample(tr["idx"], tr["logit"], tr["count"], c["u_sample"][b].numpy().reshape(w.gamma, 1))
-        O.verify_chain_seq(target[b], w.T, tr["idx"], tr["logit"], tr["count"], smp["token"][:, 0],
-                           c["u_accept"][b].numpy(), c["u_resample"][b].numpy())
+        smp = O.sample(tr["idx"], tr["logit"], tr["count"], host_set["u_sample"][b].numpy().reshape(w.gamma, 1))
+        O.verify_chain_seq(target[b].float().numpy(), w.T, tr["idx"], tr["logit"], tr["count"], smp["token"][:, 0],
+                           host_set["u_accept"][b].numpy(), host_set["u_resample"][b].numpy())
         done += 1
-        if time.perf_counter() - t0 > 25.0:
+        if time.perf_counter() - t0 > budget_s:
             break
     dt = time.perf_counter() - t0
-    return {"value": done * w.gamma / dt, "unit": "draft positions/s", "cores": 1, "kind": "oracle",
-            "sample": f"{done} sequences x gamma={w.gamma} of the same workload (truncate+sample+verify, "
-                      f"NumPy fp64, single thread), {dt:.1f} s"}
+    return {"value": round(done * w.gamma / dt, 2), "unit": "draft positions/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {done} of the {w.B} sequences (x gamma={w.gamma} positions) of input set 0 of the same "
+                      f"workload: truncate+sample+verify, NumPy fp64, one thread, {dt:.1f} s"}
 
 
 def main():
@@ -81,10 +76,13 @@ def main():
     ap.add_argument("--sets", type=int, default=3, help="independent input sets rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="time the steps without per-kernel events")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
+                    help="after the timed steps run N plain elementwise copies of 1 GiB (read 1 GiB, write 1 GiB): "
+                         "the launches that scale a profiler's FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (sequences would shard across GPUs with no exchange; "
-              "see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (sequences would shard across GPUs with no exchange); "
+              "run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -180,8 +178,16 @@ def main():
         "hbm_frac_whole_step": round(alg["total"] / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
         "kernels": kernels, "roofline": roofline,
     }
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.copy_calibration):
+            torch.mul(src, 1.0, out=dst)          # one elementwise kernel: 2^30 bytes in, 2^30 bytes out
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w, 100)
+        host = {k: v.cpu() for k, v in sets[0].items() if torch.is_tensor(v)}
+        res["cpu_baseline"] = cpu_baseline(w, host)
     print(json.dumps(res))
 
 
