@@ -8,6 +8,8 @@
 // fp64 is needed for the sampling: at V >= 128k the buckets of the inverse CDF are far narrower than
 // fp32 prefix sums can resolve.
 #pragma once
+#include <algorithm>
+#include <type_traits>
 #include "common.h"
 #include "exp64.h"
 
@@ -15,7 +17,9 @@ namespace tslt {
 
 constexpr int kSegVecs = 4;                         // 16-byte vectors per thread in a sweep segment
 constexpr int kSegVecsTotal = kSegVecs * kBlock;    // vectors per segment
-constexpr int kSubChunks = kSegVecs * kWaves;       // runs of 64 consecutive vectors per segment
+constexpr int kRunVecs = kSegVecs * 64;             // a run: the consecutive vectors one wave holds
+constexpr int kSubChunks = kWaves;                  // runs per segment
+constexpr int kAccDepth = 3;                        // batches in flight per thread in eval_row_on_set
 constexpr int kSetPer = 1024 / kBlock;              // set entries per thread (TSLT_MAX_K_CAP / kBlock)
 
 struct SegResult {       // one segment (or edge piece) of a row that is being sampled
@@ -36,9 +40,82 @@ struct VerifyShared {
   double bcast_d[4];
   int bcast_i[4];
   double piece_val[kBlock];        // level 1: mass of every piece (n_pieces <= kBlock)
-  double sub_val[kSubChunks];      // level 2: mass of every run of 64 vectors of the chosen segment
-  double elem_corr[64 * 8];        // level 3: sparse correction per element of the chosen run
+  double sub_val[kSubChunks];      // level 2: mass of every run of the chosen segment
 };
+
+// A table of exp(s) for every bf16 logit z with 2^-6 <= |z| < 2^7, s = fl32(z / T): the fp64 sums over
+// a bf16 row then cost one LDS read per element instead of an fp64 exponential.  Entry 2*r + sign holds
+// the value for magnitude bits kTabLo + r.  Values outside the domain (tiny, huge, -inf, NaN) are
+// evaluated directly.  Terms are referenced to 0 rather than to the row maximum, which is safe while
+// |s| <= kTabMaxS; a segment that holds a larger |s| is redone by the maximum-referenced path.
+constexpr int kTabLo = (127 - 6) << 7;
+constexpr int kTabSpan = 13 << 7;
+constexpr int kTabEntries = 2 * kTabSpan;
+constexpr size_t kTabBytes = size_t(kTabEntries + 2) * sizeof(double);   // + two NaN entries for "not covered"
+constexpr float kTabMaxS = 600.0f;
+inline bool exp_table_usable(float rT) { return 128.0f * rT <= kTabMaxS; }
+
+// Workgroups of a sweep launch: a few per compute unit, each looping over its share of the segments.
+inline int64_t sweep_grid_limit() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    cus = 256;
+  return int64_t(cus) * 4;
+}
+
+__device__ __forceinline__ void build_exp_table(double* table, float rT) {
+  for (int i = threadIdx.x; i < kTabEntries; i += kBlock) {
+    const uint32_t bits = (uint32_t(i & 1) << 15) | uint32_t(kTabLo + (i >> 1));
+    table[i] = exp64(double(__fmul_rn(__uint_as_float(bits << 16), rT)));
+  }
+  if (threadIdx.x < 2) table[kTabEntries + threadIdx.x] = __longlong_as_double(0x7FF8000000000000ll);
+  __syncthreads();
+}
+
+// exp(s) of one bf16 element given by its 16 bits, for the elements the table does not cover; -1 for
+// NaN or +inf, -2 for a value that needs the maximum-referenced path
+__device__ __noinline__ double exp_term_bf16(uint32_t b, float rT) {
+  const uint32_t m = b & 0x7FFFu;
+  if (m > 0x7F80u || b == 0x7F80u) return -1.0;
+  if (b == 0xFF80u) return 0.0;                                     // -inf: probability 0
+  const float s = __fmul_rn(__uint_as_float(b << 16), rT);
+  if (fabsf(s) > kTabMaxS) return -2.0;
+  return exp64(double(s));
+}
+
+// Sum of exp(s) over the 8 bf16 elements of a vector through the table.  An element outside the
+// table's domain reads a NaN entry, which shows in the sum; the vector is then redone element by element.
+__device__ __forceinline__ double table_vec_sum(const uint4& d, const double* table, float rT, int& flags) {
+  const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+  double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    uint32_t r0 = (w[k] & 0x7FFFu) - uint32_t(kTabLo);
+    uint32_t r1 = ((w[k] >> 16) & 0x7FFFu) - uint32_t(kTabLo);
+    r0 = r0 < uint32_t(kTabSpan) ? r0 : uint32_t(kTabSpan);
+    r1 = r1 < uint32_t(kTabSpan) ? r1 : uint32_t(kTabSpan);
+    s0 += table[r0 * 2 + ((w[k] >> 15) & 1u)];
+    s1 += table[r1 * 2 + (w[k] >> 31)];
+  }
+  double s = s0 + s1;
+  if (s != s) {
+    s = 0.0;
+#pragma unroll 1
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t b = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+      const uint32_t r = (b & 0x7FFFu) - uint32_t(kTabLo);
+      double t = 0.0;
+      if (r < uint32_t(kTabSpan)) t = table[r * 2 + (b >> 15)];
+      else {
+        t = exp_term_bf16(b, rT);
+        if (t < 0.0) { flags |= int(-t); t = 0.0; }
+      }
+      s += t;
+    }
+  }
+  return s;
+}
 
 // ---------------------------------------------------------------------------------------------
 // One pass over a target row: partial sums of exp2(t*k2 - c), c referenced to the largest target
@@ -64,6 +141,20 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
   const int tid = threadIdx.x;
   const int n_edge = rs.head + rs.tail;
   const int64_t n_tiles = (rs.nvec + kBlock - 1) / kBlock;
+  // The pass keeps kAccDepth batches of U vectors in flight per thread; the first ones are requested
+  // before anything else, so that they travel while the reference is looked up.
+  constexpr int U = 4;
+  const uint32_t n_full = uint32_t(rs.nvec / (U * kBlock));      // batches of U complete tiles
+  uint4 pipe[kAccDepth][U];
+  auto issue = [&](uint32_t b, uint4 (&q)[U]) {
+    const uint4* src = rs.body + size_t(b) * (U * kBlock) + tid;
+#pragma unroll
+    for (int u = 0; u < U; ++u) q[u] = load_vec_stream(src + u * kBlock);
+  };
+#pragma unroll
+  for (int s = 0; s < kAccDepth; ++s)
+    if (uint32_t(s) < n_full) issue(uint32_t(s), pipe[s]);
+
   float tv[kSetPer];       // raw target logit at entry
   float gmax = -INFINITY;
 #pragma unroll
@@ -92,20 +183,12 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
     // fp32 sums only within a batch of U vectors: a long-lived fp32 accumulator that has met one large
     // term rounds away the many small ones that follow, always downwards
     double dacc = 0.0;
-    constexpr int U = 4;
-    for (int64_t t0 = 0; t0 < n_tiles; t0 += U) {
-      uint4 d[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int64_t vi = (t0 + u) * kBlock + tid;
-        d[u] = neg_inf_vec<T>();
-        if (vi < rs.nvec) d[u] = load_vec_stream(&rs.body[vi]);
-      }
+    auto consume = [&](const uint4 (&q)[U]) {
       float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         float v[E];
-        unpack<T>(d[u], v);
+        unpack<T>(q[u], v);
 #pragma unroll
         for (int e = 0; e < E; e += 4) {
           acc0 += fast_exp2(scaled_arg(v[e + 0], k2, neg_c));
@@ -115,6 +198,25 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
         }
       }
       dacc += double((acc0 + acc1) + (acc2 + acc3));
+    };
+    for (uint32_t b = 0; b < n_full; b += kAccDepth) {
+#pragma unroll
+      for (int s = 0; s < kAccDepth; ++s) {
+        if (b + s < n_full) {
+          consume(pipe[s]);
+          if (b + s + kAccDepth < n_full) issue(b + s + kAccDepth, pipe[s]);
+        }
+      }
+    }
+    for (int64_t t0 = int64_t(n_full) * U; t0 < n_tiles; t0 += U) {      // the ragged end
+      uint4 d[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t vi = (t0 + u) * kBlock + tid;
+        d[u] = neg_inf_vec<T>();
+        if (vi < rs.nvec) d[u] = load_vec_stream(&rs.body[vi]);
+      }
+      consume(d);
     }
     if (tid < n_edge) dacc += double(fast_exp2(scaled_arg(load_elem<T>(row, edge_index<T>(rs, tid)), k2, neg_c)));
     z_c = block_sum_f64<kWaves>(dacc, sh.red);
@@ -187,75 +289,127 @@ template <typename T> __device__ __forceinline__ int piece_of(const RowSplit& rs
 }
 
 // ---------------------------------------------------------------------------------------------
-// fp64 sweep of segment `seg` of a row (all 256 threads of a workgroup): segs[1 + seg] and the
-// kSubChunks run sums of the segment; the workgroup of segment 0 also does the two edge pieces.
+// fp64 sweep of a row that has to be sampled, in segments of kSegVecsTotal vectors.  Wave w holds run w
+// of a segment: kRunVecs consecutive vectors, vector i*64 + lane in slot i.  A piece (segment or edge)
+// reports (sum, smax), meaning a mass of sum * exp(smax), and every run its mass in the same units.
 // `check` asks for NaN / +inf detection (rows that no earlier kernel has validated).
 // ---------------------------------------------------------------------------------------------
+constexpr int kGroupSegs = 4;     // consecutive segments a workgroup takes at a time
+
 template <typename T>
-__device__ __forceinline__ void sweep_segment(const void* row, const RowSplit& rs, int seg, bool check, float rT,
-                                              SegResult* segs, double* subs, VerifyShared& sh) {
-  constexpr int E = ElemTraits<T>::kPerVec;
-  const int tid = threadIdx.x;
-  const int n_seg_row = int((rs.nvec + kSegVecsTotal - 1) / kSegVecsTotal);
-  if (seg < n_seg_row) {
-    // ---- this workgroup's segment, held in registers: maximum first, then the fp64 sums
-    uint4 d[kSegVecs];
-    const int64_t vbase = int64_t(seg) * kSegVecsTotal;
+__device__ __forceinline__ void load_segment(const RowSplit& rs, int seg, uint4 (&d)[kSegVecs]) {
+  const int64_t vbase = int64_t(seg) * kSegVecsTotal + wave_id() * kRunVecs + lane_id();
 #pragma unroll
-    for (int i = 0; i < kSegVecs; ++i) {
-      const int64_t vi = vbase + int64_t(i) * kBlock + tid;
-      d[i] = neg_inf_vec<T>();
-      if (vi < rs.nvec) d[i] = load_vec(&rs.body[vi]);
+  for (int i = 0; i < kSegVecs; ++i) {
+    const int64_t vi = vbase + i * 64;
+    d[i] = neg_inf_vec<T>();
+    if (vi < rs.nvec) d[i] = load_vec(&rs.body[vi]);
+  }
+}
+
+// One segment with every term an fp64 exponential referenced to the segment's own maximum.
+template <typename T>
+__device__ __forceinline__ void sweep_segment_direct(const RowSplit& rs, int seg, bool check, float rT,
+                                                     SegResult* segs, double* subs, VerifyShared& sh) {
+  constexpr int E = ElemTraits<T>::kPerVec;
+  uint4 d[kSegVecs];
+  load_segment<T>(rs, seg, d);
+  float vmax = -INFINITY;
+  int bad = 0;
+#pragma unroll
+  for (int i = 0; i < kSegVecs; ++i) {
+    float v[E];
+    unpack<T>(d[i], v);
+    if (check) {
+#pragma unroll
+      for (int e = 0; e < E; ++e) bad |= (v[e] != v[e] || v[e] == INFINITY) ? 1 : 0;
     }
-    // this segment's own maximum is the reference of its sums
-    float vmax = -INFINITY;
-    int bad = 0;
+#pragma unroll
+    for (int e = 0; e < E; e += 2) vmax = max3f(vmax, v[e], v[e + 1]);
+  }
+  vmax = block_max_f32<kWaves>(vmax, sh.red);
+  bad = __syncthreads_or(bad);
+  const float smax = __fmul_rn(vmax, rT);      // scaling is monotone: the largest s is at the largest t
+  double run = 0.0;
+  if (smax > -INFINITY && !bad) {
+    const double m = double(smax);
 #pragma unroll
     for (int i = 0; i < kSegVecs; ++i) {
       float v[E];
       unpack<T>(d[i], v);
-      if (check) {
+      double s0 = 0.0, s1 = 0.0;
 #pragma unroll
-        for (int e = 0; e < E; ++e) bad |= (v[e] != v[e] || v[e] == INFINITY) ? 1 : 0;
+      for (int e = 0; e < E; e += 2) {            // -inf gives exactly 0
+        s0 += exp64(double(__fmul_rn(v[e], rT)) - m);
+        s1 += exp64(double(__fmul_rn(v[e + 1], rT)) - m);
       }
-#pragma unroll
-      for (int e = 0; e < E; e += 2) vmax = max3f(vmax, v[e], v[e + 1]);
-    }
-    vmax = block_max_f32<kWaves>(vmax, sh.red);
-    bad = __syncthreads_or(bad);
-    const float smax = __fmul_rn(vmax, rT);      // scaling is monotone: the largest s is at the largest t
-    subs += size_t(seg) * kSubChunks;
-    double sum = 0.0;
-    if (smax > -INFINITY && !bad) {
-      const double m = double(smax);
-#pragma unroll
-      for (int i = 0; i < kSegVecs; ++i) {
-        float v[E];
-        unpack<T>(d[i], v);
-        double s0 = 0.0, s1 = 0.0;
-#pragma unroll
-        for (int e = 0; e < E; e += 2) {            // -inf gives exactly 0
-          s0 += exp64(double(__fmul_rn(v[e], rT)) - m);
-          s1 += exp64(double(__fmul_rn(v[e + 1], rT)) - m);
-        }
-        const double run_sum = wave_sum_f64(s0 + s1);   // run (i, wave): 64 consecutive vectors
-        if (lane_id() == 0) subs[i * kWaves + wave_id()] = run_sum;
-        sum += run_sum;
-      }
-    } else if (tid < kSubChunks) {
-      subs[tid] = 0.0;
-    }
-    // every lane of a wave holds its wave's total
-    __syncthreads();
-    if (lane_id() == 0) sh.red.d[wave_id()] = sum;
-    __syncthreads();
-    if (tid == 0) {
-      double t = 0.0;
-      for (int w = 0; w < kWaves; ++w) t += sh.red.d[w];
-      segs[1 + seg].sum = t; segs[1 + seg].smax = smax; segs[1 + seg].bad = bad;
+      run += s0 + s1;
     }
   }
-  if (seg == 0 && tid == 0) {
+  const double run_sum = wave_sum_f64(run);
+  __syncthreads();
+  if (lane_id() == 0) { subs[size_t(seg) * kSubChunks + wave_id()] = run_sum; sh.red.d[wave_id()] = run_sum; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kWaves; ++w) t += sh.red.d[w];
+    segs[1 + seg].sum = t; segs[1 + seg].smax = smax; segs[1 + seg].bad = bad;
+  }
+  __syncthreads();
+}
+
+// Segments group*kGroupSegs .. +kGroupSegs-1 of a row (all 256 threads of a workgroup); group 0 also does
+// the two edge pieces.  `table` is the bf16 exp table in LDS or null.  Through the table the terms are
+// referenced to 0: a segment then reports smax = 0 (-inf if it has no mass).
+template <typename T>
+__device__ __forceinline__ void sweep_group(const void* row, const RowSplit& rs, int group, bool check, float rT,
+                                            const double* table, SegResult* segs, double* subs, VerifyShared& sh) {
+  constexpr int E = ElemTraits<T>::kPerVec;
+  const int tid = threadIdx.x;
+  const int n_seg_row = int((rs.nvec + kSegVecsTotal - 1) / kSegVecsTotal);
+  const int seg0 = group * kGroupSegs;
+  const int n_here = n_seg_row - seg0 < kGroupSegs ? n_seg_row - seg0 : kGroupSegs;   // may be <= 0
+  bool direct = n_here > 0;
+  if constexpr (std::is_same<T, Bf16>::value) {
+    if (table != nullptr && n_here > 0) {
+      int flags = 0;
+      uint4 d[kSegVecs], dn[kSegVecs];
+      load_segment<T>(rs, seg0, d);
+#pragma unroll
+      for (int k = 0; k < kGroupSegs; ++k) {
+        if (k < n_here) {
+          if (k + 1 < n_here) load_segment<T>(rs, seg0 + k + 1, dn);
+          const int64_t vbase = int64_t(seg0 + k) * kSegVecsTotal + wave_id() * kRunVecs + lane_id();
+          double run = 0.0;
+#pragma unroll
+          for (int i = 0; i < kSegVecs; ++i)
+            if (vbase + i * 64 < rs.nvec) run += table_vec_sum(d[i], table, rT, flags);
+          const double run_sum = wave_sum_f64(run);
+          if (lane_id() == 0) {
+            subs[size_t(seg0 + k) * kSubChunks + wave_id()] = run_sum;
+            sh.red.d[k * kWaves + wave_id()] = run_sum;
+          }
+          if (k + 1 < n_here) {
+#pragma unroll
+            for (int i = 0; i < kSegVecs; ++i) d[i] = dn[i];
+          }
+        }
+      }
+      flags = block_or_i32<kWaves>(flags, sh.red);      // its barriers also publish the run sums
+      direct = (flags & 2) != 0;
+      if (!direct && tid < n_here) {
+        const int bad = (flags & 1) && check ? 1 : 0;
+        double t = 0.0;
+        for (int w = 0; w < kWaves; ++w) t += sh.red.d[tid * kWaves + w];
+        SegResult& o = segs[1 + seg0 + tid];
+        o.sum = bad ? 0.0 : t; o.smax = (t > 0.0 && !bad) ? 0.0f : -INFINITY; o.bad = bad;
+      }
+      __syncthreads();
+    }
+  }
+  if (direct)
+    for (int k = 0; k < n_here; ++k) sweep_segment_direct<T>(rs, seg0 + k, check, rT, segs, subs, sh);
+  if (group == 0 && tid == 0) {
     // the two edge pieces (at most E-1 elements each)
     for (int piece = 0; piece < 2; ++piece) {
       const int e0 = piece == 0 ? 0 : rs.head, e1 = piece == 0 ? rs.head : rs.head + rs.tail;
@@ -305,8 +459,9 @@ template <typename T>
 __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st) {
   constexpr int E = ElemTraits<T>::kPerVec;
   constexpr int kMaxPer = kSetPer;
-  constexpr int kRun = 64 * E;              // elements in a run of 64 vectors
-  constexpr int kPerT = kRun / kBlock;      // elements per thread at level 3
+  constexpr int kRun = kRunVecs * E;        // elements in a run
+  constexpr int kPerT = kRun / kBlock;      // consecutive elements per thread at level 3 (one vector)
+  __shared__ double elem_corr[kRunVecs * 8];   // level 3: sparse correction per element of the chosen run
   const int tid = threadIdx.x;
   const RowSplit& rs = a.rs;
   const void* row = a.row;
@@ -435,13 +590,13 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st) {
       // an edge piece: fewer than E elements, walked by one thread
       {
         const int e0 = piece == 0 ? 0 : rs.head;
-        if (tid < 2 * E) sh.elem_corr[tid] = 0.0;
+        if (tid < 2 * E) elem_corr[tid] = 0.0;
         __syncthreads();
 #pragma unroll
         for (int k = 0; k < kMaxPer; ++k)
           if (yi[k] >= 0 && piece_of<T>(rs, n_seg_row, yi[k]) == piece) {
             const int e = yi[k] < rs.head ? yi[k] : rs.head + int(yi[k] - (rs.head + rs.nvec * E));
-            sh.elem_corr[e - e0] = corr[k];
+            elem_corr[e - e0] = corr[k];
           }
         __syncthreads();
       }
@@ -453,7 +608,7 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st) {
           const float t = load_elem<T>(row, y);
           double v = t > -INFINITY ? exp64(double(__fmul_rn(t, rT)) - double(smax)) : 0.0;
           if (use_corr) {
-            v += sh.elem_corr[e - e0];
+            v += elem_corr[e - e0];
             if (v < 0.0) v = 0.0;
           }
           if (v > 0.0) {
@@ -467,7 +622,7 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st) {
       __syncthreads();
       token = sh.bcast_i[3];
     } else if (piece > 0) {
-      // ---- level 2: which run of 64 consecutive vectors of the body segment ------------------------
+      // ---- level 2: which run of the body segment ------------------------
       const int seg = piece - 1;
       const int64_t seg_first_vec = int64_t(seg) * kSegVecsTotal;
       const int64_t seg_first_elem = rs.head + seg_first_vec * E;
@@ -495,7 +650,7 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st) {
         sh.bcast_i[1] = sub;
         sh.bcast_d[1] = before;
       }
-      for (int i = tid; i < kRun; i += kBlock) sh.elem_corr[i] = 0.0;
+      for (int i = tid; i < kRun; i += kBlock) elem_corr[i] = 0.0;
       __syncthreads();
       const int sub = sh.bcast_i[1];
       const double before_run = sh.bcast_d[1];
@@ -504,7 +659,7 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st) {
         const int64_t run_first = seg_first_elem + int64_t(sub) * kRun;
 #pragma unroll
         for (int k = 0; k < kMaxPer; ++k)
-          if (yi[k] >= run_first && yi[k] < run_first + kRun) sh.elem_corr[yi[k] - run_first] = corr[k];
+          if (yi[k] >= run_first && yi[k] < run_first + kRun) elem_corr[yi[k] - run_first] = corr[k];
         __syncthreads();
         double v[kPerT];
         double mine = 0.0;
@@ -514,7 +669,7 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st) {
           v[q] = 0.0;
           if ((y - rs.head) / E < rs.nvec) {
             const float t = load_elem<T>(row, y);
-            v[q] = exp64(double(__fmul_rn(t, rT)) - double(smax)) + sh.elem_corr[tid * kPerT + q];
+            v[q] = exp64(double(__fmul_rn(t, rT)) - double(smax)) + elem_corr[tid * kPerT + q];
             if (v[q] < 0.0) v[q] = 0.0;
           }
           mine += v[q];

@@ -52,6 +52,7 @@ struct TreeParams {
   int tasks;              // rows sampled per tree: n_nodes (all nodes) or 1 (path only)
   int all_nodes;
   int n_seg, n_seg_grid;
+  int use_table;          // kernel S sums bf16 rows through the exp table
 };
 
 inline size_t tree_workspace_bytes(int64_t B, int64_t n_nodes, int64_t V, bool all_nodes) {
@@ -191,16 +192,26 @@ __global__ __launch_bounds__(64) void tree_walk_kernel(const TreeParams p) {
 template <typename T>
 __global__ __launch_bounds__(kBlock) void tree_sweep_kernel(const TreeParams p) {
   __shared__ VerifyShared sh;
-  const int64_t task = blockIdx.x / p.n_seg_grid;              // (b, t)
-  const int seg = int(blockIdx.x - task * p.n_seg_grid);
-  const int64_t b = task / p.tasks;
-  const int node = p.all_nodes ? int(task - b * p.tasks) : p.term_node[b];
-  if (node < p.n_int && p.node_state[b * p.n_int + node] != 0) return;   // accepted a child, or unusable
-  const void* row = tree_row<T>(p, b, node);
-  const RowSplit rs = split_row<T>(row, p.V);
-  // non-leaf rows were validated by kernel M; leaves are seen here for the first time
-  sweep_segment<T>(row, rs, seg, node >= p.n_int, p.rT, p.segs + size_t(task) * (p.n_seg + 2),
-                   p.subs + size_t(task) * p.n_seg * kSubChunks, sh);
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  double* table = nullptr;
+  if (std::is_same<T, Bf16>::value && p.use_table) {
+    table = reinterpret_cast<double*>(dyn_lds);
+    build_exp_table(table, p.rT);
+  }
+  const int64_t n_items = p.B * p.tasks * p.n_seg_grid;
+  for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {      // persistent workgroups
+    const int64_t task = item / p.n_seg_grid;                    // (b, t)
+    const int seg = int(item - task * p.n_seg_grid);
+    const int64_t b = task / p.tasks;
+    const int node = p.all_nodes ? int(task - b * p.tasks) : p.term_node[b];
+    if (node < p.n_int && p.node_state[b * p.n_int + node] != 0) continue;   // accepted a child, or unusable
+    const void* row = tree_row<T>(p, b, node);
+    const RowSplit rs = split_row<T>(row, p.V);
+    // non-leaf rows were validated by kernel M; leaves are seen here for the first time
+    sweep_group<T>(row, rs, seg, node >= p.n_int, p.rT, table, p.segs + size_t(task) * (p.n_seg + 2),
+                     p.subs + size_t(task) * p.n_seg * kSubChunks, sh);
+    __syncthreads();
+  }
 }
 
 template <typename T>
@@ -259,8 +270,10 @@ template <typename T> hipError_t launch_verify_tree(TreeParams p, hipStream_t s)
   const int E = ElemTraits<T>::kPerVec;
   int n_seg = int((p.V / E + 1 + kSegVecsTotal - 1) / kSegVecsTotal);
   if (n_seg > p.n_seg) n_seg = p.n_seg;
-  p.n_seg_grid = n_seg;
-  hipLaunchKernelGGL(tree_sweep_kernel<T>, dim3(unsigned(p.B * p.tasks * n_seg)), dim3(kBlock), 0, s, p);
+  p.n_seg_grid = (n_seg + kGroupSegs - 1) / kGroupSegs;
+  p.use_table = std::is_same<T, Bf16>::value && exp_table_usable(p.rT) ? 1 : 0;
+  const int64_t grid = std::min<int64_t>(p.B * p.tasks * p.n_seg_grid, sweep_grid_limit());
+  hipLaunchKernelGGL(tree_sweep_kernel<T>, dim3(unsigned(grid)), dim3(kBlock), p.use_table ? kTabBytes : 0, s, p);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(tree_finish_kernel<T>, dim3(unsigned(p.B * p.tasks)), dim3(kBlock), 0, s, p);
   if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -18,7 +18,8 @@
 
 namespace tslt {
 
-constexpr int kBatch = 4;      // tiles per batch; the first batch is the threshold sample
+constexpr int kBatch = 4;        // tiles per batch; the first batch is the threshold sample
+constexpr int kDepth = 3;        // batches in flight per thread during the pass
 constexpr int kRing = 48;      // pairs of vectors a wave can park; expanded when a third full
 
 struct TruncateParams {
@@ -390,6 +391,24 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
         if (vi < nvec) d[u] = load_vec_stream(&rs.body[vi]);
       }
     }
+    // The pass keeps kDepth batches in flight per thread; the first ones are requested now, so that they
+    // travel while the threshold is being worked out.  The first tile of a sample batch is not read again.
+    uint4 pipe[kDepth][kBatch];
+    const uint32_t n_pipe = long_row ? n_full : 0;
+    uint32_t skip_b = 0, skips_left = kBatch;
+    const uint32_t stride_b = s_stride / kBatch;
+    auto issue = [&](uint32_t b, uint4 (&q)[kBatch]) {
+      const uint4* src = rs.body + size_t(b) * (kBatch * kBlock) + tid;
+      const bool skip = skips_left > 0 && b == skip_b;
+      if (skip) { skip_b += stride_b; --skips_left; }
+      q[0] = neg_inf_vec<T>();
+      if (!skip) q[0] = load_vec_stream(src);
+#pragma unroll
+      for (int u = 1; u < kBatch; ++u) q[u] = load_vec_stream(src + u * kBlock);
+    };
+#pragma unroll
+    for (int s = 0; s < kDepth; ++s)
+      if (uint32_t(s) < n_pipe) issue(uint32_t(s), pipe[s]);
     float tmax = -INFINITY;
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
@@ -491,22 +510,19 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
       }
       uint32_t first_generic_tile = kBatch;             // short rows: everything after the sample tiles
       if (long_row) {
-        // complete batches; the first tile of a batch is left out when it was a sample tile
-        uint32_t skip_b = 0, skips_left = kBatch;
-        const uint32_t stride_b = s_stride / kBatch;
-        const uint4* src = rs.body + tid;
-        for (uint32_t b = 0; b < n_full; ++b, src += kBatch * kBlock) {
-          const bool skip = skips_left > 0 && b == skip_b;
-          if (skip) { skip_b += stride_b; --skips_left; }
-          d[0] = neg_inf_vec<T>();
-          if (!skip) d[0] = load_vec_stream(src);
-          d[1] = load_vec_stream(src + kBlock);
-          d[2] = load_vec_stream(src + 2 * kBlock);
-          d[3] = load_vec_stream(src + 3 * kBlock);
-          const uint32_t v0 = b * (kBatch * kBlock) + tid;
-          process_pair(d[0], d[1], v0, v0 + kBlock);
-          process_pair(d[2], d[3], v0 + 2 * kBlock, v0 + 3 * kBlock);
-          flush();
+        // complete batches
+        for (uint32_t b = 0; b < n_pipe; b += kDepth) {
+#pragma unroll
+          for (int s = 0; s < kDepth; ++s) {
+            const uint32_t bb = b + s;
+            if (bb < n_pipe) {
+              const uint32_t v0 = bb * (kBatch * kBlock) + tid;
+              process_pair(pipe[s][0], pipe[s][1], v0, v0 + kBlock);
+              process_pair(pipe[s][2], pipe[s][3], v0 + 2 * kBlock, v0 + 3 * kBlock);
+              flush();
+              if (bb + kDepth < n_pipe) issue(bb + kDepth, pipe[s]);
+            }
+          }
         }
         first_generic_tile = n_full * kBatch;
       }

@@ -35,9 +35,10 @@ struct VerifyParams {
   int32_t* flags;        // [B, gamma] 1 accepted, 0 rejected, 2 row unusable
   int32_t* row_status;   // [B, gamma]
   SegResult* segs;       // [B, n_seg + 2]
-  double* subs;          // [B, n_seg, kSubChunks] sums of exp(s - smax of the segment) per run of 64 vectors
+  double* subs;          // [B, n_seg, kSubChunks] mass of every run of a segment, in the segment's units
   int n_seg;             // body segments per row (upper bound used for the layout)
-  int n_seg_grid;        // workgroups of kernel B1 per sequence
+  int n_seg_grid;        // segment groups of kernel B1 per sequence
+  int use_table;         // kernel B1 sums bf16 rows through the exp table
 };
 
 inline size_t verify_workspace_bytes(int64_t B, int64_t gamma, int64_t V, int k_cap) {
@@ -133,19 +134,31 @@ __device__ __forceinline__ int first_rejection(const VerifyParams& p, int64_t b,
   return jstar;
 }
 
+// Workgroups are persistent: each builds the exp table once (bf16 rows) and then takes the
+// (sequence, segment group) items blockIdx.x, blockIdx.x + gridDim.x, ...
 template <typename T>
 __global__ __launch_bounds__(kBlock) void verify_sweep_kernel(const VerifyParams p) {
   __shared__ VerifyShared sh;
-  const int n_seg_grid = p.n_seg_grid;      // workgroups per sequence (layout bound; rows may need fewer)
-  const int64_t b = blockIdx.x / n_seg_grid;
-  const int seg = int(blockIdx.x - b * n_seg_grid);
-  const int jstar = first_rejection(p, b, sh);
-  if (jstar < p.gamma && p.flags[b * p.gamma + jstar] == 2) return;     // unusable row: nothing to sample
-  const void* row = target_row<T>(p, b, jstar);
-  const RowSplit rs = split_row<T>(row, p.V);
-  // a row that kernel A has accepted or rejected has been validated there; the bonus row is checked here
-  sweep_segment<T>(row, rs, seg, jstar == p.gamma, p.rT, p.segs + size_t(b) * (p.n_seg + 2),
-                   p.subs + size_t(b) * p.n_seg * kSubChunks, sh);
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  double* table = nullptr;
+  if (std::is_same<T, Bf16>::value && p.use_table) {
+    table = reinterpret_cast<double*>(dyn_lds);
+    build_exp_table(table, p.rT);
+  }
+  const int n_seg_grid = p.n_seg_grid;      // segment groups per sequence (layout bound; rows may need fewer)
+  const int64_t n_items = p.B * n_seg_grid;
+  for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const int64_t b = item / n_seg_grid;
+    const int seg = int(item - b * n_seg_grid);
+    const int jstar = first_rejection(p, b, sh);
+    if (jstar < p.gamma && p.flags[b * p.gamma + jstar] == 2) continue;   // unusable row: nothing to sample
+    const void* row = target_row<T>(p, b, jstar);
+    const RowSplit rs = split_row<T>(row, p.V);
+    // a row that kernel A has accepted or rejected has been validated there; the bonus row is checked here
+    sweep_group<T>(row, rs, seg, jstar == p.gamma, p.rT, table, p.segs + size_t(b) * (p.n_seg + 2),
+                     p.subs + size_t(b) * p.n_seg * kSubChunks, sh);
+    __syncthreads();
+  }
 }
 
 template <typename T>
@@ -201,8 +214,10 @@ template <typename T> hipError_t launch_verify(VerifyParams p, hipStream_t s, in
     const int E = ElemTraits<T>::kPerVec;
     int n_seg = int((p.V / E + 1 + kSegVecsTotal - 1) / kSegVecsTotal);
     if (n_seg > p.n_seg) n_seg = p.n_seg;
-    p.n_seg_grid = n_seg;
-    hipLaunchKernelGGL(verify_sweep_kernel<T>, dim3(unsigned(p.B * n_seg)), dim3(kBlock), 0, s, p);
+    p.n_seg_grid = (n_seg + kGroupSegs - 1) / kGroupSegs;
+    p.use_table = std::is_same<T, Bf16>::value && exp_table_usable(p.rT) ? 1 : 0;
+    const int64_t grid = std::min<int64_t>(p.B * p.n_seg_grid, sweep_grid_limit());
+    hipLaunchKernelGGL(verify_sweep_kernel<T>, dim3(unsigned(grid)), dim3(kBlock), p.use_table ? kTabBytes : 0, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(verify_finish_kernel<T>, dim3(unsigned(p.B)), dim3(kBlock), 0, s, p);
     e = hipGetLastError();
