@@ -122,6 +122,24 @@ int tslt_sample(const int32_t* idx, const float* logit, const int32_t* count, in
                 int32_t k_cap, const float* u, int32_t n_samples, int32_t without_replacement,
                 int32_t* out_token, int32_t* out_slot, void* stream);
 
+/* "Sparsify-then-sample" (Solution 1 of Section 3.2) in one launch: tslt_truncate followed by n_samples
+ * i.i.d. draws from each row's q_hat (Algorithm 4's candidate draws; n_samples = 1 for a chain), with the
+ * same results as tslt_truncate followed by tslt_sample(..., without_replacement = 0).
+ *
+ *   arguments up to `status`   as for tslt_truncate
+ *   u           [rows, n_samples] fp32 uniforms in [0,1)
+ *   n_samples   1..TSLT_MAX_BRANCH
+ *   out_token   [rows, n_samples] int32 sampled token ids (-1 if the row's set is empty)
+ *   out_slot    [rows, n_samples] int32 position of the token inside its set; may be NULL
+ * Workspace: none.
+ */
+int tslt_truncate_sample(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
+                         float temperature, int32_t top_k, float top_p, int32_t k_cap,
+                         int32_t* out_idx, float* out_logit, float* out_prob, int32_t* out_count,
+                         float* out_mass, int32_t* status,
+                         const float* u, int32_t n_samples, int32_t* out_token, int32_t* out_slot,
+                         void* ws, size_t ws_bytes, void* stream);
+
 /* Token-sequence verification (Algorithm 3) for B sequences of gamma draft positions.
  *
  *   target_logits [B, gamma+1, row_stride] target logits; row gamma is the bonus row P_{L+1}

@@ -181,6 +181,18 @@ template <int NW> __device__ __forceinline__ int block_sum_i32(int v, BlockScrat
   return t;
 }
 
+template <int NW> __device__ __forceinline__ int block_max_i32(int v, BlockScratch& s) {
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) { const int o = __shfl_xor(v, m, 64); v = o > v ? o : v; }
+  __syncthreads();
+  if (lane_id() == 0) s.i[wave_id()] = v;
+  __syncthreads();
+  int t = s.i[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) t = s.i[w] > t ? s.i[w] : t;
+  return t;
+}
+
 template <int NW> __device__ __forceinline__ int block_or_i32(int v, BlockScratch& s) {
 #pragma unroll
   for (int m = 32; m > 0; m >>= 1) v |= __shfl_xor(v, m, 64);

@@ -42,6 +42,11 @@ struct TruncateParams {
   int32_t* out_count;
   float* out_mass;
   int32_t* status;
+  // optional draws from q_hat in the same launch (null u = none)
+  const float* u;    // [rows, n_samples]
+  int n_samples;
+  int32_t* out_token;
+  int32_t* out_slot;
 };
 
 // Dynamic LDS: [ rings ] [ candidates, then sort scratch ].  The ring space is
@@ -359,16 +364,32 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
   const int lane = lane_id();
   const int wave = wave_id();
   const int64_t row_i = blockIdx.x;
+  // The sample: the first tile of kBatch batches at equal distances; a row with fewer than 4*kBatch
+  // complete batches uses its first kBatch tiles.
+  auto load_sample = [&](const RowSplit& r, uint4 (&q)[kBatch]) {
+    const uint32_t nv = uint32_t(r.nvec);
+    const uint32_t nf = nv / (kBatch * kBlock);
+    if (nf >= 4) {
+      const uint32_t stride = (nf / 4) * kBatch;
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) q[u] = load_vec_stream(&r.body[u * stride * kBlock + tid]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const uint32_t vi = u * kBlock + tid;
+        q[u] = neg_inf_vec<T>();
+        if (vi < nv) q[u] = load_vec_stream(&r.body[vi]);
+      }
+    }
+  };
   const void* row = reinterpret_cast<const char*>(p.logits) + size_t(row_i) * size_t(p.row_stride) * ElemTraits<T>::kBytes;
   const RowSplit rs = split_row<T>(row, p.V);
   const int n_edge = rs.head + rs.tail;
   const uint32_t nvec = uint32_t(rs.nvec);
   const uint32_t n_tiles = (nvec + kBlock - 1) / kBlock;
   const uint32_t n_full = nvec / (kBatch * kBlock);        // batches of kBatch complete, consecutive tiles
-  // The sample: the first tile of kBatch batches at equal distances; a row with fewer than 4*kBatch
-  // complete batches uses its first kBatch tiles.
   const bool long_row = n_full >= 4;
-  const uint32_t s_stride = long_row ? (n_full / 4) * kBatch : 1;   // in tiles
+  const uint32_t s_stride = long_row ? (n_full / 4) * kBatch : 1;   // distance of the sample tiles, in tiles
 
   int st = 0;
   int n_cand = 0;
@@ -380,31 +401,31 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
   if (fast_ok) {
     // ---- the sample: per-thread maxima ----------------------------------------------------------
     uint4 d[kBatch];
-    if (long_row) {
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) d[u] = load_vec_stream(&rs.body[u * s_stride * kBlock + tid]);
-    } else {
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const uint32_t vi = u * kBlock + tid;
-        d[u] = neg_inf_vec<T>();
-        if (vi < nvec) d[u] = load_vec_stream(&rs.body[vi]);
-      }
-    }
+    load_sample(rs, d);
     // The pass keeps kDepth batches in flight per thread; the first ones are requested now, so that they
     // travel while the threshold is being worked out.  The first tile of a sample batch is not read again.
+    // A long row's ragged end (fewer than kBatch tiles, the last one possibly incomplete) is one more batch.
     uint4 pipe[kDepth][kBatch];
-    const uint32_t n_pipe = long_row ? n_full : 0;
+    const uint32_t n_pipe = long_row ? n_full + (n_tiles > n_full * kBatch ? 1u : 0u) : 0u;
     uint32_t skip_b = 0, skips_left = kBatch;
     const uint32_t stride_b = s_stride / kBatch;
     auto issue = [&](uint32_t b, uint4 (&q)[kBatch]) {
-      const uint4* src = rs.body + size_t(b) * (kBatch * kBlock) + tid;
-      const bool skip = skips_left > 0 && b == skip_b;
-      if (skip) { skip_b += stride_b; --skips_left; }
-      q[0] = neg_inf_vec<T>();
-      if (!skip) q[0] = load_vec_stream(src);
+      const uint32_t v0 = b * (kBatch * kBlock) + tid;
+      if (b < n_full) {
+        const uint4* src = rs.body + v0;
+        const bool skip = skips_left > 0 && b == skip_b;
+        if (skip) { skip_b += stride_b; --skips_left; }
+        q[0] = neg_inf_vec<T>();
+        if (!skip) q[0] = load_vec_stream(src);
 #pragma unroll
-      for (int u = 1; u < kBatch; ++u) q[u] = load_vec_stream(src + u * kBlock);
+        for (int u = 1; u < kBatch; ++u) q[u] = load_vec_stream(src + u * kBlock);
+      } else {
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          q[u] = neg_inf_vec<T>();
+          if (v0 + u * kBlock < nvec) q[u] = load_vec_stream(&rs.body[v0 + u * kBlock]);
+        }
+      }
     };
 #pragma unroll
     for (int s = 0; s < kDepth; ++s)
@@ -524,9 +545,9 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
             }
           }
         }
-        first_generic_tile = n_full * kBatch;
+        first_generic_tile = n_tiles;
       }
-      // what is left: tiles that may be incomplete
+      // short rows: the tiles after the sample, which may be incomplete
       for (uint32_t t = first_generic_tile; t < n_tiles; t += 2) {
         const uint32_t v0 = t * kBlock + tid, v1 = v0 + kBlock;
         d[0] = neg_inf_vec<T>();
@@ -662,6 +683,33 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
     p.out_count[row_i] = count;
     if (p.out_mass) p.out_mass[row_i] = count > 0 ? float(c_sel / Z) : 0.0f;
     if (p.status) p.status[row_i] = st;
+  }
+  // ---- draws from q_hat: the first entry whose inclusive prefix exceeds u * (mass of the kept set) ---
+  if (p.u) {
+    for (int c = 0; c < p.n_samples; ++c) {
+      const size_t o = size_t(row_i) * p.n_samples + c;
+      const double target = double(p.u[o]) * c_sel;
+      int not_above = 0, last_pos = -1;
+      double run = excl;
+#pragma unroll
+      for (int r = 0; r < kMaxPer; ++r) {
+        const int i = tid * per + r;
+        if (r < per && i < count) {
+          run += e64[r];
+          not_above += run > target ? 0 : 1;
+          if (e64[r] > 0.0) last_pos = i;
+        }
+      }
+      int slot = count > 0 ? block_sum_i32<kWaves>(not_above, sh.red) : -1;
+      if (slot >= count) slot = block_max_i32<kWaves>(last_pos, sh.red);   // only for u >= 1 (uniform branch)
+#pragma unroll
+      for (int r = 0; r < kMaxPer; ++r)
+        if (r < per && tid * per + r == slot) p.out_token[o] = int32_t(idx[r]);
+      if (tid == 0) {
+        if (slot < 0) p.out_token[o] = -1;
+        if (p.out_slot) p.out_slot[o] = slot;
+      }
+    }
   }
 }
 

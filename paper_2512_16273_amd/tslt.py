@@ -21,7 +21,7 @@ OP_TRUNCATE, OP_SAMPLE, OP_VERIFY, OP_VERIFY_TREE, OP_VERIFY_TREE_PATH = 0, 1, 2
 ROW_NONFINITE, ROW_EMPTY, ROW_TOKEN_NOT_IN_SET, ROW_EXACT_PATH = 1, 2, 4, 256
 MAX_K_CAP = 1024
 
-EXPORTS = ("tslt_version", "tslt_last_error", "tslt_workspace_bytes", "tslt_truncate", "tslt_sample",
+EXPORTS = ("tslt_version", "tslt_last_error", "tslt_workspace_bytes", "tslt_truncate", "tslt_truncate_sample", "tslt_sample",
            "tslt_verify", "tslt_verify_accept", "tslt_verify_resample", "tslt_verify_tree")
 
 _lib = None
@@ -51,6 +51,9 @@ def load(path: Optional[str] = None):
     lib.tslt_workspace_bytes.argtypes = [c.c_int, i64, i64, i64, i32]
     lib.tslt_truncate.restype = c.c_int
     lib.tslt_truncate.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tslt_truncate_sample.restype = c.c_int
+    lib.tslt_truncate_sample.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, f32, i32, vp, vp, vp, vp, vp, vp,
+                                         vp, i32, vp, vp, vp, sz, vp]
     lib.tslt_sample.restype = c.c_int
     lib.tslt_sample.argtypes = [vp, vp, vp, i64, i32, vp, i32, i32, vp, vp, vp]
     for fn in (lib.tslt_verify, lib.tslt_verify_accept, lib.tslt_verify_resample):
@@ -118,9 +121,10 @@ def _workspace(nbytes: int, device) -> Optional[torch.Tensor]:
 
 
 def truncate(logits: torch.Tensor, temperature: float, top_k: int, top_p: float, k_cap: int,
-             want_prob: bool = True, out: Optional[dict] = None) -> dict:
+             want_prob: bool = True, out: Optional[dict] = None, u: Optional[torch.Tensor] = None) -> dict:
     """tslt_truncate over logits [..., V].  Returns idx, logit, prob, count, mass, status ([rows, k_cap] /
-    [rows])."""
+    [rows]).  With uniforms u [rows, n] it is tslt_truncate_sample: the result also holds token, slot
+    [rows, n], n i.i.d. draws from each row's q_hat."""
     lib = load()
     _dev(logits, name="logits", contiguous=False)
     rows, V, stride = _rows_2d(logits)
@@ -134,9 +138,22 @@ def truncate(logits: torch.Tensor, temperature: float, top_k: int, top_p: float,
             "mass": torch.empty(rows, dtype=torch.float32, device=dev),
             "status": torch.empty(rows, dtype=torch.int32, device=dev),
         }
-    _check(lib.tslt_truncate(_ptr(logits), _dtype_code(logits), rows, V, stride, float(temperature), int(top_k),
-                             float(top_p), int(k_cap), _ptr(out["idx"]), _ptr(out["logit"]), _ptr(out.get("prob")),
-                             _ptr(out["count"]), _ptr(out.get("mass")), _ptr(out.get("status")), None, 0, _stream()))
+    if u is None:
+        _check(lib.tslt_truncate(_ptr(logits), _dtype_code(logits), rows, V, stride, float(temperature), int(top_k),
+                                 float(top_p), int(k_cap), _ptr(out["idx"]), _ptr(out["logit"]), _ptr(out.get("prob")),
+                                 _ptr(out["count"]), _ptr(out.get("mass")), _ptr(out.get("status")), None, 0, _stream()))
+        return out
+    _dev(u, torch.float32, "u")
+    u2 = u.reshape(rows, -1)
+    n = u2.shape[1]
+    if "token" not in out:
+        out["token"] = torch.empty(rows, n, dtype=torch.int32, device=dev)
+        out["slot"] = torch.empty(rows, n, dtype=torch.int32, device=dev)
+    _check(lib.tslt_truncate_sample(_ptr(logits), _dtype_code(logits), rows, V, stride, float(temperature), int(top_k),
+                                    float(top_p), int(k_cap), _ptr(out["idx"]), _ptr(out["logit"]),
+                                    _ptr(out.get("prob")), _ptr(out["count"]), _ptr(out.get("mass")),
+                                    _ptr(out.get("status")), _ptr(u2), n, _ptr(out["token"]), _ptr(out.get("slot")),
+                                    None, 0, _stream()))
     return out
 
 

@@ -107,6 +107,49 @@ def test_sample_matches_oracle(tslt, wo):
     assert torch.all(out["token"] == -1)
 
 
+@pytest.mark.parametrize("name,V,rows,T,top_k,top_p,k_cap,n", [
+    ("bf16-topp-1", 32000, 24, 0.8, 0, 0.95, 256, 1),
+    ("bf16-topk-4", 20011, 19, 0.8, 32, 0.0, 32, 4),
+    ("f32-topk-3", 5000, 9, 1.0, 16, 0.0, 16, 3),
+    ("bf16-k1024-2", 70000, 6, 1.0, 0, 0.999, 1024, 2),
+    ("bf16-k3-16", 9000, 5, 1.0, 3, 0.0, 4, 16),
+])
+def test_truncate_sample_in_one_launch(tslt, name, V, rows, T, top_k, top_p, k_cap, n):
+    """tslt_truncate_sample: the truncation against the oracle as for tslt_truncate; the draws against the
+    oracle's sampling from the very sets the call returned, and against tslt_sample on those sets."""
+    w = W.scaled(W.WORKLOADS["chain_topk"], V=V, dtype="f32" if name.startswith("f32") else "bf16")
+    z = rows_like(w, rows, 21)
+    u = W.uniforms((rows, n), 9, 2, 3, DEV)
+    out = tslt.truncate(z, T, top_k, top_p, k_cap, u=u)
+    torch.cuda.synchronize()
+    P.compare_truncate({k: v for k, v in out.items() if k not in ("token", "slot")}, z, T, top_k, top_p, k_cap, label=name)
+    want = O.sample(P.to_np(out["idx"]), P.to_np(out["logit"]), P.to_np(out["count"]), P.to_np(u), False)
+    assert np.array_equal(P.to_np(out["slot"]), want["slot"]), name
+    assert np.array_equal(P.to_np(out["token"]), want["token"]), name
+    two = tslt.sample(out["idx"], out["logit"], out["count"], u, False)
+    assert torch.equal(two["token"], out["token"]) and torch.equal(two["slot"], out["slot"])
+
+
+def test_truncate_sample_degenerate_and_errors(tslt):
+    V = 3000
+    z = torch.randn(4, V, generator=torch.Generator().manual_seed(2)).to(torch.bfloat16)
+    z[1] = -float("inf")                      # nothing to draw from
+    z[2, 7] = float("nan")
+    z[3, 10:] = -float("inf")                 # 10 finite logits, K = 16
+    z = z.to(DEV)
+    u = torch.tensor([[0.0, 0.999999], [0.5, 0.5], [0.5, 0.5], [0.0, 0.999999]], dtype=torch.float32, device=DEV)
+    out = tslt.truncate(z, 1.0, 16, 0.0, 16, u=u)
+    torch.cuda.synchronize()
+    tok, slot, cnt = P.to_np(out["token"]), P.to_np(out["slot"]), P.to_np(out["count"])
+    assert cnt[1] == 0 and cnt[2] == 0 and cnt[3] == 10
+    assert np.all(tok[1] == -1) and np.all(tok[2] == -1) and np.all(slot[1] == -1)
+    want = O.sample(P.to_np(out["idx"]), P.to_np(out["logit"]), cnt, P.to_np(u), False)
+    assert np.array_equal(tok, want["token"]) and np.array_equal(slot, want["slot"])
+    assert slot[0, 0] == 0 and slot[3, 1] <= 9
+    with pytest.raises(tslt.TsltError):
+        tslt.truncate(z, 1.0, 16, 0.0, 16, u=torch.zeros(4, 17, dtype=torch.float32, device=DEV))
+
+
 def test_tiny_config_end_to_end_truncate(tslt):
     w = W.WORKLOADS["tiny"]
     c = W.make_chain(w, 0, DEV)
