@@ -81,7 +81,7 @@ const char* tslt_last_error(void);
 
 /* Bytes of workspace an operation needs.  `n_outer` is the number of rows (truncate, sample) or of
  * sequences B (verify, verify_tree); `n_inner` is gamma (verify) or N_nodes (verify_tree), ignored
- * otherwise.  Returns 0 when the operation needs none. */
+ * otherwise.  Returns 0 when the operation uses none. */
 size_t tslt_workspace_bytes(int op, int64_t n_outer, int64_t n_inner, int64_t V, int32_t k_cap);
 
 /* Truncated sampling on logits (Section 3.1; Solution 1 of Section 3.2), one draft row per position.

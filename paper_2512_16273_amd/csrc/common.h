@@ -253,54 +253,64 @@ template <int NW> __device__ __forceinline__ int block_excl_scan_i32(int v, Bloc
 // returns false, leaving `in` intact, when tmp_cap is too small for that.  `in` and `out` may be the
 // same array; `tmp` must be distinct from both.  hist, start and cursor are 256-entry LDS arrays.
 // Work per thread is about n/256 + k_keep/256 * mean bin population; values crowded into one bin cost
-// more, bounded by n^2/256 comparisons per thread.  Needs a 256-thread workgroup.
+// more, bounded by n^2/256 comparisons per thread.  NT = threads of the workgroup (64, 128 or 256).
 __device__ __forceinline__ int value_bin(uint64_t c, double vmin, double scale) {
   const int b = int((double(cand_value(c)) - vmin) * scale);
   return b > 255 ? 255 : b;
 }
+template <int NT>
 __device__ __forceinline__ bool bucket_sort_desc(const uint64_t* in, int n, uint64_t* tmp, int tmp_cap, uint64_t* out,
                                                  int k_keep, uint32_t* hist, uint32_t* start, uint32_t* cursor,
                                                  BlockScratch& red) {
+  constexpr int NW = NT / 64;
+  constexpr int BPT = 256 / NT;      // bins per thread: thread t owns bins 255 - t*BPT - j, j < BPT
   if (n <= 0) return true;
   const int tid = threadIdx.x;
   uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
-  for (int i = tid; i < n; i += kBlock) {
+  for (int i = tid; i < n; i += NT) {
     const uint32_t k = uint32_t(in[i] >> 32);
     kmin = k < kmin ? k : kmin;
     kmax = k > kmax ? k : kmax;
   }
   kmax = wave_max_u32(kmax);
   kmin = ~wave_max_u32(~kmin);
-  hist[tid] = 0;
+  for (int b = tid; b < 256; b += NT) hist[b] = 0;
   if (lane_id() == 0) { red.i[wave_id()] = int(kmin); red.i[8 + wave_id()] = int(kmax); }
   __syncthreads();
   kmin = uint32_t(red.i[0]); kmax = uint32_t(red.i[8]);
 #pragma unroll
-  for (int w = 1; w < kWaves; ++w) {
+  for (int w = 1; w < NW; ++w) {
     kmin = uint32_t(red.i[w]) < kmin ? uint32_t(red.i[w]) : kmin;
     kmax = uint32_t(red.i[8 + w]) > kmax ? uint32_t(red.i[8 + w]) : kmax;
   }
   const double vmin = double(key_to_f32(kmin));
   const double span = double(key_to_f32(kmax)) - vmin;
   const double scale = (span > 0.0 && span < 1e300) ? 255.0 / span : 0.0;
-  for (int i = tid; i < n; i += kBlock) atomicAdd(&hist[value_bin(in[i], vmin, scale)], 1u);
+  for (int i = tid; i < n; i += NT) atomicAdd(&hist[value_bin(in[i], vmin, scale)], 1u);
   __syncthreads();
   int total;
-  const int mine = int(hist[255 - tid]);
-  const int excl = block_excl_scan_i32<kWaves>(mine, red, total);   // bins in descending order
-  start[255 - tid] = uint32_t(excl);
-  cursor[255 - tid] = uint32_t(excl);
-  // records in the bins that start before place k_keep
-  const int n_moved = block_sum_i32<kWaves>(excl < k_keep ? mine : 0, red);
+  int h[BPT], mine = 0;
+#pragma unroll
+  for (int j = 0; j < BPT; ++j) { h[j] = int(hist[255 - tid * BPT - j]); mine += h[j]; }
+  const int excl = block_excl_scan_i32<NW>(mine, red, total);   // bins in descending order
+  int run = excl, moved = 0;
+#pragma unroll
+  for (int j = 0; j < BPT; ++j) {
+    start[255 - tid * BPT - j] = uint32_t(run);
+    cursor[255 - tid * BPT - j] = uint32_t(run);
+    if (run < k_keep) moved += h[j];      // records in the bins that start before place k_keep
+    run += h[j];
+  }
+  const int n_moved = block_sum_i32<NW>(moved, red);
   if (n_moved > tmp_cap) return false;
   __syncthreads();
-  for (int i = tid; i < n; i += kBlock) {
+  for (int i = tid; i < n; i += NT) {
     const uint64_t c = in[i];
     const int b = value_bin(c, vmin, scale);
     if (int(start[b]) < k_keep) tmp[atomicAdd(&cursor[b], 1u)] = c;
   }
   __syncthreads();
-  for (int i = tid; i < n_moved; i += kBlock) {
+  for (int i = tid; i < n_moved; i += NT) {
     const uint64_t c = tmp[i];
     const int b = value_bin(c, vmin, scale);
     const int s0 = int(start[b]);

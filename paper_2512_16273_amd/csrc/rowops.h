@@ -44,14 +44,16 @@ struct VerifyShared {
 };
 
 // A table of exp(s) for every bf16 logit z with 2^-6 <= |z| < 2^7, s = fl32(z / T): the fp64 sums over
-// a bf16 row then cost one LDS read per element instead of an fp64 exponential.  Entry 2*r + sign holds
-// the value for magnitude bits kTabLo + r.  Values outside the domain (tiny, huge, -inf, NaN) are
-// evaluated directly.  Terms are referenced to 0 rather than to the row maximum, which is safe while
-// |s| <= kTabMaxS; a segment that holds a larger |s| is redone by the maximum-referenced path.
+// a bf16 row then cost one LDS read per element instead of an fp64 exponential.  With the 16 bits of an
+// element rotated left by one (sign in bit 0), entry 1 + (rotated - 2*kTabLo) holds its value; entries 0
+// and kTabEntries + 1 hold NaN and stand for everything below and above the table's domain (tiny, huge,
+// -inf, NaN), which is evaluated directly.  Terms are referenced to 0 rather than to the row maximum,
+// which is safe while |s| <= kTabMaxS; a segment that holds a larger |s| is redone by the
+// maximum-referenced path.
 constexpr int kTabLo = (127 - 6) << 7;
 constexpr int kTabSpan = 13 << 7;
 constexpr int kTabEntries = 2 * kTabSpan;
-constexpr size_t kTabBytes = size_t(kTabEntries + 2) * sizeof(double);   // + two NaN entries for "not covered"
+constexpr size_t kTabBytes = size_t(kTabEntries + 2) * sizeof(double);
 constexpr float kTabMaxS = 600.0f;
 inline bool exp_table_usable(float rT) { return 128.0f * rT <= kTabMaxS; }
 
@@ -64,13 +66,15 @@ inline int64_t sweep_grid_limit() {
   return int64_t(cus) * 4;
 }
 
-__device__ __forceinline__ void build_exp_table(double* table, float rT) {
-  for (int i = threadIdx.x; i < kTabEntries; i += kBlock) {
-    const uint32_t bits = (uint32_t(i & 1) << 15) | uint32_t(kTabLo + (i >> 1));
-    table[i] = exp64(double(__fmul_rn(__uint_as_float(bits << 16), rT)));
-  }
-  if (threadIdx.x < 2) table[kTabEntries + threadIdx.x] = __longlong_as_double(0x7FF8000000000000ll);
-  __syncthreads();
+__device__ __forceinline__ double exp_table_entry(int i, float rT) {
+  if (i < 1 || i > kTabEntries) return __longlong_as_double(0x7FF8000000000000ll);
+  const int j = i - 1;
+  const uint32_t bits = (uint32_t(j & 1) << 15) | uint32_t(kTabLo + (j >> 1));
+  return exp64(double(__fmul_rn(__uint_as_float(bits << 16), rT)));
+}
+// Fills the table with all `threads` threads of the workgroup; the caller synchronises.
+__device__ __forceinline__ void build_exp_table(double* table, float rT, int threads) {
+  for (int i = threadIdx.x; i < kTabEntries + 2; i += threads) table[i] = exp_table_entry(i, rT);
 }
 
 // exp(s) of one bf16 element given by its 16 bits, for the elements the table does not cover; -1 for
@@ -84,19 +88,26 @@ __device__ __noinline__ double exp_term_bf16(uint32_t b, float rT) {
   return exp64(double(s));
 }
 
-// Sum of exp(s) over the 8 bf16 elements of a vector through the table.  An element outside the
-// table's domain reads a NaN entry, which shows in the sum; the vector is then redone element by element.
+// Sum of exp(s) over the 8 bf16 elements of a vector through the table.  The index arithmetic runs on
+// both halves of a 32-bit word at once (16-bit lanes: rotate, saturating subtract, minimum, scale by 8).
+// An element outside the table's domain reads a NaN entry, which shows in the sum; the vector is then
+// redone element by element.
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ double table_vec_sum(const uint4& d, const double* table, float rT, int& flags) {
   const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+  const char* tb = reinterpret_cast<const char*>(table);
+  const ushort2_t base = {uint16_t(2 * kTabLo - 1), uint16_t(2 * kTabLo - 1)};
+  const ushort2_t top = {uint16_t(kTabEntries + 1), uint16_t(kTabEntries + 1)};
+  const ushort2_t three = {3, 3};
   double s0 = 0.0, s1 = 0.0;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
-    uint32_t r0 = (w[k] & 0x7FFFu) - uint32_t(kTabLo);
-    uint32_t r1 = ((w[k] >> 16) & 0x7FFFu) - uint32_t(kTabLo);
-    r0 = r0 < uint32_t(kTabSpan) ? r0 : uint32_t(kTabSpan);
-    r1 = r1 < uint32_t(kTabSpan) ? r1 : uint32_t(kTabSpan);
-    s0 += table[r0 * 2 + ((w[k] >> 15) & 1u)];
-    s1 += table[r1 * 2 + (w[k] >> 31)];
+    const uint32_t rot = ((w[k] << 1) & 0xFFFEFFFEu) | ((w[k] >> 15) & 0x00010001u);
+    ushort2_t i2 = __builtin_elementwise_sub_sat(__builtin_bit_cast(ushort2_t, rot), base);
+    i2 = __builtin_elementwise_min(i2, top) << three;
+    const uint32_t off = __builtin_bit_cast(uint32_t, i2);
+    s0 += *reinterpret_cast<const double*>(tb + (off & 0xFFFFu));
+    s1 += *reinterpret_cast<const double*>(tb + (off >> 16));
   }
   double s = s0 + s1;
   if (s != s) {
@@ -106,7 +117,7 @@ __device__ __forceinline__ double table_vec_sum(const uint4& d, const double* ta
       const uint32_t b = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
       const uint32_t r = (b & 0x7FFFu) - uint32_t(kTabLo);
       double t = 0.0;
-      if (r < uint32_t(kTabSpan)) t = table[r * 2 + (b >> 15)];
+      if (r < uint32_t(kTabSpan)) t = table[1 + r * 2 + (b >> 15)];
       else {
         t = exp_term_bf16(b, rT);
         if (t < 0.0) { flags |= int(-t); t = 0.0; }

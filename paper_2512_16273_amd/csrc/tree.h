@@ -196,7 +196,8 @@ __global__ __launch_bounds__(kBlock) void tree_sweep_kernel(const TreeParams p) 
   double* table = nullptr;
   if (std::is_same<T, Bf16>::value && p.use_table) {
     table = reinterpret_cast<double*>(dyn_lds);
-    build_exp_table(table, p.rT);
+    build_exp_table(table, p.rT, kBlock);
+    __syncthreads();
   }
   const int64_t n_items = p.B * p.tasks * p.n_seg_grid;
   for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {      // persistent workgroups

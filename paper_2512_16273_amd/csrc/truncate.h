@@ -18,8 +18,9 @@
 
 namespace tslt {
 
+constexpr int kTruncThreads = 256;   // threads of a truncate workgroup (one row each)
 constexpr int kBatch = 4;        // tiles per batch; the first batch is the threshold sample
-constexpr int kDepth = 3;        // batches in flight per thread during the pass
+constexpr int kDepth = 2;        // batches in flight per thread during the pass
 constexpr int kRing = 48;      // pairs of vectors a wave can park; expanded when a third full
 
 struct TruncateParams {
@@ -34,7 +35,7 @@ struct TruncateParams {
   int tau_bits;      // number of leading key bits resolved by the threshold search
   int sort_cap;      // capacity of the candidate array
   int lds_recs;      // records that fit in the candidate region; those past sort_cap are sort scratch
-  int ring_bytes;    // size of the ring space at the start of dynamic LDS (>= kRingBytes)
+  int ring_bytes;    // size of the ring space at the start of dynamic LDS (ring_bytes_for the workgroup's waves)
   int tmp_in_ring;   // the sort scratch is the ring space behind the tables
   int32_t* out_idx;
   float* out_logit;
@@ -52,9 +53,9 @@ struct TruncateParams {
 // Dynamic LDS: [ rings ] [ candidates, then sort scratch ].  The ring space is
 // reused for the sort's three 256-entry tables and, before the pass, for the per-thread sample maxima.
 constexpr int kHitList = 192;   // positions a wave can collect in one expansion (a ring holds kRing * 16 elements)
-constexpr int kRingBytes = kWaves * (kRing * 40 + kHitList * 2);
-static_assert(kRingBytes >= 3 * 256 * 4, "ring space must hold the sort tables");
-inline size_t truncate_lds_bytes(int lds_recs) { return size_t(kRingBytes) + size_t(8) * lds_recs; }
+constexpr int ring_bytes_for(int n_waves) { return n_waves * (kRing * 40 + kHitList * 2); }
+static_assert(ring_bytes_for(2) >= 3 * 256 * 4, "ring space must hold the sort tables");
+inline size_t truncate_lds_bytes(int ring_bytes, int lds_recs) { return size_t(ring_bytes) + size_t(8) * lds_recs; }
 inline int truncate_sort_scratch(int k_sel) { return k_sel + k_sel / 2 + 64; }   // records the sort may need
 
 struct TruncateShared {
@@ -71,21 +72,22 @@ struct TruncateShared {
 // Also recomputes the fp32 sum with the true maximum as reference.  Returns the number of
 // candidates written to cand[] (exactly k_eff), or 0 with `st` set.
 // ---------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, int NT>
 __device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uint64_t* cand, uint32_t* hist,
                             TruncateShared& sh, float& c_ref, double& z_c, int& st) {
+  constexpr int NW = NT / 64;
   const int tid = threadIdx.x;
   // pass 1: validity, number of selectable elements, maximum
   int fin = 0, bad = 0;
   float vmax = -INFINITY;
-  for (int64_t i = tid; i < V; i += kBlock) {
+  for (int64_t i = tid; i < V; i += NT) {
     float v = load_elem<T>(row, i);
     if (v != v || v == INFINITY) bad = 1;
     else if (v > -INFINITY) { ++fin; vmax = fmaxf(vmax, v); }
   }
-  bad = block_sum_i32<kWaves>(bad, sh.red);
-  fin = block_sum_i32<kWaves>(fin, sh.red);
-  vmax = block_max_f32<kWaves>(vmax, sh.red);
+  bad = block_sum_i32<NW>(bad, sh.red);
+  fin = block_sum_i32<NW>(fin, sh.red);
+  vmax = block_max_f32<NW>(vmax, sh.red);
   if (bad) { st |= 1; return 0; }
   if (fin == 0) { st |= 2; return 0; }
   const int k_eff = k_sel < fin ? k_sel : fin;
@@ -94,10 +96,10 @@ __device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uin
   uint32_t prefix = 0;
   int need = k_eff;
   for (int shift = 24; shift >= 0; shift -= 8) {
-    hist[tid] = 0;
+    for (int b = tid; b < 256; b += NT) hist[b] = 0;
     __syncthreads();
     const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
-    for (int64_t i = tid; i < V; i += kBlock) {
+    for (int64_t i = tid; i < V; i += NT) {
       float v = load_elem<T>(row, i);
       uint32_t key = mono_key(v + 0.0f);
       if (v > -INFINITY && (key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
@@ -125,7 +127,7 @@ __device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uin
   __syncthreads();
   int eq_base = 0;
   constexpr int kChunk = 8;
-  for (int64_t base = 0; base < V; base += int64_t(kBlock) * kChunk) {
+  for (int64_t base = 0; base < V; base += int64_t(NT) * kChunk) {
     uint32_t eq_mask = 0;
     const int64_t i0 = base + int64_t(tid) * kChunk;
 #pragma unroll
@@ -145,7 +147,7 @@ __device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uin
       }
     }
     int total;
-    int off = block_excl_scan_i32<kWaves>(__popc(eq_mask), sh.red, total);
+    int off = block_excl_scan_i32<NW>(__popc(eq_mask), sh.red, total);
     if (eq_base < need) {
       int ord = eq_base + off;
 #pragma unroll
@@ -164,8 +166,8 @@ __device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uin
   // the normaliser's fp32 partial sums, referenced to the true maximum
   c_ref = __fmul_rn(vmax, k2);
   double acc = 0.0;
-  for (int64_t i = tid; i < V; i += kBlock) acc += double(fast_exp2(__builtin_fmaf(load_elem<T>(row, i), k2, -c_ref)));
-  z_c = block_sum_f64<kWaves>(acc, sh.red);
+  for (int64_t i = tid; i < V; i += NT) acc += double(fast_exp2(__builtin_fmaf(load_elem<T>(row, i), k2, -c_ref)));
+  z_c = block_sum_f64<NW>(acc, sh.red);
   __syncthreads();
   return k_eff;
 }
@@ -178,28 +180,32 @@ __device__ int exact_select(const void* row, int64_t V, int k_sel, float k2, uin
 // row is full of ties.  Pass 2 collects them.  Returns the number of candidates, 0 with `st` set for
 // an unusable row, or -1 when the candidates do not fit (then the radix selection is used).
 // ---------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, int NT>
 __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, float k2, uint64_t* cand, int cap,
                                uint64_t* sort_tmp, int sort_tmp_cap, uint32_t* tables, TruncateShared& sh,
                                bool need_sum, float& c_ref, double& z_c, int& st) {
   constexpr int E = ElemTraits<T>::kPerVec;
+  constexpr int NW = NT / 64;
+  constexpr int GPT = 1024 / NT;       // groups per thread
   const int tid = threadIdx.x;
   const int n_edge = rs.head + rs.tail;
-  const int64_t n_tiles = (rs.nvec + kBlock - 1) / kBlock;
-  if (cap < 4 * kBlock + 2 * E) return -1;
+  const int64_t n_tiles = (rs.nvec + NT - 1) / NT;
+  if (cap < GPT * NT + 2 * E) return -1;
   // pass 1
-  float gmax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-  int fin = 0, bad = 0;
-  for (int64_t t0 = 0; t0 < n_tiles; t0 += 4) {
-    uint4 d[4];
+  float gmax[GPT];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int64_t vi = (t0 + u) * kBlock + tid;
+  for (int u = 0; u < GPT; ++u) gmax[u] = -INFINITY;
+  int fin = 0, bad = 0;
+  for (int64_t t0 = 0; t0 < n_tiles; t0 += GPT) {
+    uint4 d[GPT];
+#pragma unroll
+    for (int u = 0; u < GPT; ++u) {
+      const int64_t vi = (t0 + u) * NT + tid;
       d[u] = neg_inf_vec<T>();
       if (vi < rs.nvec) d[u] = load_vec(&rs.body[vi]);
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < GPT; ++u) {
       float v[E];
       unpack<T>(d[u], v);
 #pragma unroll
@@ -218,25 +224,27 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
     bad |= (edge_v != edge_v || edge_v == INFINITY) ? 1 : 0;
     fin += edge_v > -INFINITY ? 1 : 0;
   }
-  bad = block_or_i32<kWaves>(bad, sh.red);
-  fin = block_sum_i32<kWaves>(fin, sh.red);
+  bad = block_or_i32<NW>(bad, sh.red);
+  fin = block_sum_i32<NW>(fin, sh.red);
   if (bad) { st |= 1; return 0; }
   if (fin == 0) { st |= 2; return 0; }
   const int k_eff = k_sel < fin ? k_sel : fin;
-  float vmax = fmaxf(fmaxf(gmax[0], gmax[1]), fmaxf(gmax[2], gmax[3]));
-  vmax = block_max_f32<kWaves>(fmaxf(vmax, edge_v), sh.red);
+  float vmax = gmax[0];
+#pragma unroll
+  for (int u = 1; u < GPT; ++u) vmax = fmaxf(vmax, gmax[u]);
+  vmax = block_max_f32<NW>(fmaxf(vmax, edge_v), sh.red);
   // the k_eff-th largest group maximum (edge elements are groups of their own; empty groups are left out)
   if (tid == 0) sh.cand_count = 0;
   __syncthreads();
 #pragma unroll
-  for (int u = 0; u < 4; ++u)
-    if (gmax[u] > -INFINITY) cand[atomicAdd(&sh.cand_count, 1)] = make_cand(gmax[u], uint32_t(tid * 4 + u));
-  if (tid < n_edge && edge_v > -INFINITY) cand[atomicAdd(&sh.cand_count, 1)] = make_cand(edge_v, uint32_t(4 * kBlock + tid));
+  for (int u = 0; u < GPT; ++u)
+    if (gmax[u] > -INFINITY) cand[atomicAdd(&sh.cand_count, 1)] = make_cand(gmax[u], uint32_t(tid * GPT + u));
+  if (tid < n_edge && edge_v > -INFINITY) cand[atomicAdd(&sh.cand_count, 1)] = make_cand(edge_v, uint32_t(GPT * NT + tid));
   __syncthreads();
   const int n_groups = sh.cand_count;
   float tau = -INFINITY;                               // fewer than k_eff non-empty groups: take everything
   if (n_groups >= k_eff) {
-    if (!bucket_sort_desc(cand, n_groups, sort_tmp, sort_tmp_cap, cand, k_eff, tables, tables + 256, tables + 512,
+    if (!bucket_sort_desc<NT>(cand, n_groups, sort_tmp, sort_tmp_cap, cand, k_eff, tables, tables + 256, tables + 512,
                           sh.red))
       return -1;
     tau = cand_value(cand[k_eff - 1]);
@@ -251,7 +259,7 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
     uint4 d[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int64_t vi = (t0 + u) * kBlock + tid;
+      const int64_t vi = (t0 + u) * NT + tid;
       d[u] = neg_inf_vec<T>();
       if (vi < rs.nvec) d[u] = load_vec(&rs.body[vi]);
     }
@@ -259,7 +267,7 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
     for (int u = 0; u < 4; ++u) {
       float v[E];
       unpack<T>(d[u], v);
-      const uint32_t base = uint32_t(rs.head) + uint32_t((t0 + u) * kBlock + tid) * E;
+      const uint32_t base = uint32_t(rs.head) + uint32_t((t0 + u) * NT + tid) * E;
 #pragma unroll
       for (int e = 0; e < E; ++e) {
         if (need_sum) acc += double(fast_exp2(__builtin_fmaf(v[e], k2, -c_ref)));
@@ -277,7 +285,7 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
       if (pos < cap) cand[pos] = make_cand(edge_v, uint32_t(edge_i));
     }
   }
-  if (need_sum) z_c = block_sum_f64<kWaves>(acc, sh.red);
+  if (need_sum) z_c = block_sum_f64<NW>(acc, sh.red);
   __syncthreads();
   const int n = sh.cand_count;
   __syncthreads();
@@ -344,15 +352,16 @@ template <> __device__ __forceinline__ float vec_max<Bf16>(const float (&v)[8]) 
   return max3f(max3f(max3f(v[0], v[1], v[2]), v[3], v[4]), max3f(v[5], v[6], v[7]), v[5]);
 }
 
-template <typename T>
-__global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p) {
+template <typename T, int NT>
+__global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
   constexpr int E = ElemTraits<T>::kPerVec;
+  constexpr int NW = NT / 64;
   static_assert(kBatch == 4, "the pass handles a batch as two pairs of tiles");
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ TruncateShared sh;
   RingPair* ring_all = reinterpret_cast<RingPair*>(dyn_lds);
-  uint2* ring_vidx_all = reinterpret_cast<uint2*>(dyn_lds + kWaves * kRing * 32);
-  uint16_t* hitlist_all = reinterpret_cast<uint16_t*>(dyn_lds + kWaves * kRing * 40);
+  uint2* ring_vidx_all = reinterpret_cast<uint2*>(dyn_lds + NW * kRing * 32);
+  uint16_t* hitlist_all = reinterpret_cast<uint16_t*>(dyn_lds + NW * kRing * 40);
   uint32_t* tables = reinterpret_cast<uint32_t*>(dyn_lds);          // 3 x 256 entries, aliasing the rings
   uint64_t* cand = reinterpret_cast<uint64_t*>(dyn_lds + p.ring_bytes);
   // sort scratch: what is left of the ring space behind the tables, or (if that is too small for the
@@ -368,15 +377,15 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
   // complete batches uses its first kBatch tiles.
   auto load_sample = [&](const RowSplit& r, uint4 (&q)[kBatch]) {
     const uint32_t nv = uint32_t(r.nvec);
-    const uint32_t nf = nv / (kBatch * kBlock);
+    const uint32_t nf = nv / (kBatch * NT);
     if (nf >= 4) {
       const uint32_t stride = (nf / 4) * kBatch;
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u) q[u] = load_vec_stream(&r.body[u * stride * kBlock + tid]);
+      for (int u = 0; u < kBatch; ++u) q[u] = load_vec_stream(&r.body[u * stride * NT + tid]);
     } else {
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
-        const uint32_t vi = u * kBlock + tid;
+        const uint32_t vi = u * NT + tid;
         q[u] = neg_inf_vec<T>();
         if (vi < nv) q[u] = load_vec_stream(&r.body[vi]);
       }
@@ -386,8 +395,8 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
   const RowSplit rs = split_row<T>(row, p.V);
   const int n_edge = rs.head + rs.tail;
   const uint32_t nvec = uint32_t(rs.nvec);
-  const uint32_t n_tiles = (nvec + kBlock - 1) / kBlock;
-  const uint32_t n_full = nvec / (kBatch * kBlock);        // batches of kBatch complete, consecutive tiles
+  const uint32_t n_tiles = (nvec + NT - 1) / NT;
+  const uint32_t n_full = nvec / (kBatch * NT);        // batches of kBatch complete, consecutive tiles
   const bool long_row = n_full >= 4;
   const uint32_t s_stride = long_row ? (n_full / 4) * kBatch : 1;   // distance of the sample tiles, in tiles
 
@@ -410,7 +419,7 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
     uint32_t skip_b = 0, skips_left = kBatch;
     const uint32_t stride_b = s_stride / kBatch;
     auto issue = [&](uint32_t b, uint4 (&q)[kBatch]) {
-      const uint32_t v0 = b * (kBatch * kBlock) + tid;
+      const uint32_t v0 = b * (kBatch * NT) + tid;
       if (b < n_full) {
         const uint4* src = rs.body + v0;
         const bool skip = skips_left > 0 && b == skip_b;
@@ -418,12 +427,12 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
         q[0] = neg_inf_vec<T>();
         if (!skip) q[0] = load_vec_stream(src);
 #pragma unroll
-        for (int u = 1; u < kBatch; ++u) q[u] = load_vec_stream(src + u * kBlock);
+        for (int u = 1; u < kBatch; ++u) q[u] = load_vec_stream(src + u * NT);
       } else {
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
           q[u] = neg_inf_vec<T>();
-          if (v0 + u * kBlock < nvec) q[u] = load_vec_stream(&rs.body[v0 + u * kBlock]);
+          if (v0 + u * NT < nvec) q[u] = load_vec_stream(&rs.body[v0 + u * NT]);
         }
       }
     };
@@ -440,20 +449,20 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
     tables[tid] = mono_key(tmax);
     __syncthreads();
     // ---- tau0: the jprime-th largest of the 256 per-thread sample maxima (every wave redundantly)
-    uint32_t kq[kWaves];
+    uint32_t kq[NW];
 #pragma unroll
-    for (int q = 0; q < kWaves; ++q) kq[q] = tables[lane + 64 * q];
+    for (int q = 0; q < NW; ++q) kq[q] = tables[lane + 64 * q];
     uint32_t tau_key = 0;
     for (int bit = 31; bit >= 32 - p.tau_bits; --bit) {
       const uint32_t trial = tau_key | (1u << bit);
       int cnt = 0;
 #pragma unroll
-      for (int q = 0; q < kWaves; ++q) cnt += __popcll(ballot(kq[q] >= trial));
+      for (int q = 0; q < NW; ++q) cnt += __popcll(ballot(kq[q] >= trial));
       if (cnt >= p.jprime) tau_key = trial;
     }
     uint32_t top_key = kq[0];   // the sample maximum
 #pragma unroll
-    for (int q = 1; q < kWaves; ++q) top_key = kq[q] > top_key ? kq[q] : top_key;
+    for (int q = 1; q < NW; ++q) top_key = kq[q] > top_key ? kq[q] : top_key;
     top_key = wave_max_u32(top_key);
     const float smax = key_to_f32(top_key);
     const float tau0 = tau_key <= kKeyNegInf ? -INFINITY : key_to_f32(tau_key);
@@ -525,8 +534,8 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
       // the sample tiles, already in registers
       {
         const uint32_t t1 = s_stride, t2 = 2 * s_stride, t3 = 3 * s_stride;
-        process_pair(d[0], d[1], tid, t1 * kBlock + tid);
-        process_pair(d[2], d[3], t2 * kBlock + tid, t3 * kBlock + tid);
+        process_pair(d[0], d[1], tid, t1 * NT + tid);
+        process_pair(d[2], d[3], t2 * NT + tid, t3 * NT + tid);
         flush();
       }
       uint32_t first_generic_tile = kBatch;             // short rows: everything after the sample tiles
@@ -537,9 +546,9 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
           for (int s = 0; s < kDepth; ++s) {
             const uint32_t bb = b + s;
             if (bb < n_pipe) {
-              const uint32_t v0 = bb * (kBatch * kBlock) + tid;
-              process_pair(pipe[s][0], pipe[s][1], v0, v0 + kBlock);
-              process_pair(pipe[s][2], pipe[s][3], v0 + 2 * kBlock, v0 + 3 * kBlock);
+              const uint32_t v0 = bb * (kBatch * NT) + tid;
+              process_pair(pipe[s][0], pipe[s][1], v0, v0 + NT);
+              process_pair(pipe[s][2], pipe[s][3], v0 + 2 * NT, v0 + 3 * NT);
               flush();
               if (bb + kDepth < n_pipe) issue(bb + kDepth, pipe[s]);
             }
@@ -549,7 +558,7 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
       }
       // short rows: the tiles after the sample, which may be incomplete
       for (uint32_t t = first_generic_tile; t < n_tiles; t += 2) {
-        const uint32_t v0 = t * kBlock + tid, v1 = v0 + kBlock;
+        const uint32_t v0 = t * NT + tid, v1 = v0 + NT;
         d[0] = neg_inf_vec<T>();
         d[1] = neg_inf_vec<T>();
         if (v0 < nvec) d[0] = load_vec_stream(&rs.body[v0]);
@@ -570,7 +579,7 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
         }
       }
       flush();
-      z_c = block_sum_f64<kWaves>(dacc, sh.red);
+      z_c = block_sum_f64<NW>(dacc, sh.red);
       __syncthreads();
       n_cand = sh.cand_count;
       fast_ok = !sh.overflow && n_cand <= p.sort_cap && n_cand >= p.k_sel && z_c > 0.0 && z_c < INFINITY;
@@ -581,27 +590,27 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
   if (!fast_ok) {
     st |= 256;
     const bool need_sum = !(z_c > 0.0 && z_c < INFINITY);
-    n_cand = two_pass_select<T>(row, rs, p.k_sel, p.k2, cand, p.sort_cap, sort_tmp, sort_tmp_cap, tables, sh, need_sum,
+    n_cand = two_pass_select<T, NT>(row, rs, p.k_sel, p.k2, cand, p.sort_cap, sort_tmp, sort_tmp_cap, tables, sh, need_sum,
                                 c_ref, z_c, st);
-    if (n_cand < 0) n_cand = exact_select<T>(row, p.V, p.k_sel, p.k2, cand, tables, sh, c_ref, z_c, st);
+    if (n_cand < 0) n_cand = exact_select<T, NT>(row, p.V, p.k_sel, p.k2, cand, tables, sh, c_ref, z_c, st);
   }
 
   // ---- sort the candidates into canonical order ------------------------------------------------
   __syncthreads();
-  if (!bucket_sort_desc(cand, n_cand, sort_tmp, sort_tmp_cap, cand, p.k_sel, tables, tables + 256, tables + 512,
+  if (!bucket_sort_desc<NT>(cand, n_cand, sort_tmp, sort_tmp_cap, cand, p.k_sel, tables, tables + 256, tables + 512,
                         sh.red)) {
     // the bin at the k-th place is too crowded for the scratch space (a row full of ties): radix selection
     // delivers exactly k candidates, which always fit
     st |= 256;
-    n_cand = exact_select<T>(row, p.V, p.k_sel, p.k2, cand, tables, sh, c_ref, z_c, st);
-    bucket_sort_desc(cand, n_cand, sort_tmp, sort_tmp_cap, cand, p.k_sel, tables, tables + 256, tables + 512, sh.red);
+    n_cand = exact_select<T, NT>(row, p.V, p.k_sel, p.k2, cand, tables, sh, c_ref, z_c, st);
+    bucket_sort_desc<NT>(cand, n_cand, sort_tmp, sort_tmp_cap, cand, p.k_sel, tables, tables + 256, tables + 512, sh.red);
   }
   const int k_eff = n_cand < p.k_sel ? n_cand : p.k_sel;
 
   // ---- fp64 evaluation of the kept head: Top-rho, renormalisation, outputs -----------------------
   // thread t owns entries [t*per, t*per + per) so that a block scan gives prefix masses in order
-  const int per = (k_eff + kBlock - 1) / kBlock;       // 0..4
-  constexpr int kMaxPer = 4;
+  const int per = (k_eff + NT - 1) / NT;       // 0..kMaxPer
+  constexpr int kMaxPer = 1024 / NT;
   double e64[kMaxPer];
   float s32[kMaxPer];
   uint32_t idx[kMaxPer];
@@ -626,8 +635,8 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
     }
   }
   double head64;
-  const double excl = block_excl_scan_f64<kWaves>(local, sh.red, head64);
-  head32 = block_sum_f64<kWaves>(head32, sh.red);
+  const double excl = block_excl_scan_f64<NW>(local, sh.red, head64);
+  head32 = block_sum_f64<NW>(head32, sh.red);
   // normaliser relative to the row maximum: fp32 tail rescaled to that reference + fp64 head
   double tail = z_c - head32;
   if (tail < 0.0) tail = 0.0;
@@ -646,7 +655,7 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
         below += run < thr ? 1 : 0;
       }
     }
-    below = block_sum_i32<kWaves>(below, sh.red);
+    below = block_sum_i32<NW>(below, sh.red);
     count = below + 1 < k_eff ? below + 1 : k_eff;
   }
   // mass of the kept set: inclusive prefix at entry count-1
@@ -674,7 +683,7 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
       if (p.out_prob) p.out_prob[out0 + i] = float(e64[r] / c_sel);
     }
   }
-  for (int i = count + tid; i < p.k_cap; i += kBlock) {
+  for (int i = count + tid; i < p.k_cap; i += NT) {
     p.out_idx[out0 + i] = -1;
     p.out_logit[out0 + i] = -INFINITY;
     if (p.out_prob) p.out_prob[out0 + i] = 0.0f;
@@ -700,8 +709,8 @@ __global__ __launch_bounds__(kBlock) void truncate_kernel(const TruncateParams p
           if (e64[r] > 0.0) last_pos = i;
         }
       }
-      int slot = count > 0 ? block_sum_i32<kWaves>(not_above, sh.red) : -1;
-      if (slot >= count) slot = block_max_i32<kWaves>(last_pos, sh.red);   // only for u >= 1 (uniform branch)
+      int slot = count > 0 ? block_sum_i32<NW>(not_above, sh.red) : -1;
+      if (slot >= count) slot = block_max_i32<NW>(last_pos, sh.red);   // only for u >= 1 (uniform branch)
 #pragma unroll
       for (int r = 0; r < kMaxPer; ++r)
         if (r < per && tid * per + r == slot) p.out_token[o] = int32_t(idx[r]);

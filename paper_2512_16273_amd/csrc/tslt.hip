@@ -48,10 +48,10 @@ int next_pow2(int v) {
 
 // Launch plan of the truncate kernel: which rank among the per-thread sample maxima gives the
 // threshold, and how large the candidate array has to be.  Returns the bytes of dynamic LDS.
-size_t plan_truncate(tslt_dtype dt, int64_t V, tslt::TruncateParams& p) {
+size_t plan_truncate(tslt_dtype dt, int64_t V, int nt, tslt::TruncateParams& p) {
   const int E = dt == TSLT_BF16 ? 8 : 4;
-  const double G = tslt::kBlock;
-  const int64_t tile = int64_t(tslt::kBlock) * E;
+  const double G = nt;                                 // per-thread sample maxima
+  const int64_t tile = int64_t(nt) * E;
   const int64_t n_tiles = (V + tile - 1) / tile;
   const int64_t ns = n_tiles < tslt::kBatch ? n_tiles : tslt::kBatch;
   const double n_sample = double(ns * tile < V ? ns * tile : V);
@@ -65,10 +65,10 @@ size_t plan_truncate(tslt_dtype dt, int64_t V, tslt::TruncateParams& p) {
   // candidate capacity: always room for the fallback's 1024 group maxima and for 2 * k_sel records.
   // The sort needs about 1.5 * k_sel records of scratch: the ring space behind the sort's tables if
   // that is large enough, else extra records behind the candidates.
-  const int min_cap = (4 * tslt::kBlock + 16 > 2 * p.k_sel) ? 4 * tslt::kBlock + 16 : 2 * p.k_sel;
+  const int min_cap = (1024 + 16 > 2 * p.k_sel) ? 1024 + 16 : 2 * p.k_sel;
   const int scratch = tslt::truncate_sort_scratch(p.k_sel);
-  p.ring_bytes = tslt::kRingBytes;
-  p.tmp_in_ring = (tslt::kRingBytes - 3 * 256 * 4) / 8 >= scratch ? 1 : 0;
+  p.ring_bytes = tslt::ring_bytes_for(nt / 64);
+  p.tmp_in_ring = (p.ring_bytes - 3 * 256 * 4) / 8 >= scratch ? 1 : 0;
   const int extra = p.tmp_in_ring ? 0 : scratch;
   p.sort_cap = min_cap;
   p.lds_recs = min_cap + extra;
@@ -76,13 +76,13 @@ size_t plan_truncate(tslt_dtype dt, int64_t V, tslt::TruncateParams& p) {
     const double j_eff = -G * std::log(1.0 - double(jprime) / G);
     int sort_cap = int((j_eff + 5.0 * std::sqrt(j_eff) + 4.0) / f) + 16;   // mean + 5 sigma of the hits
     if (sort_cap < min_cap) sort_cap = min_cap;
-    if (tslt::truncate_lds_bytes(sort_cap + extra) + sizeof(tslt::TruncateShared) + 256 <= kMaxLds) {
+    if (tslt::truncate_lds_bytes(p.ring_bytes, sort_cap + extra) + sizeof(tslt::TruncateShared) + 256 <= kMaxLds) {
       p.jprime = jprime;
       p.sort_cap = sort_cap;
       p.lds_recs = sort_cap + extra;
     }
   }
-  return tslt::truncate_lds_bytes(p.lds_recs);
+  return tslt::truncate_lds_bytes(p.ring_bytes, p.lds_recs);
 }
 
 template <typename K> hipError_t allow_large_lds(K kernel) {
@@ -116,7 +116,8 @@ size_t tslt_workspace_bytes(int op, int64_t n_outer, int64_t n_inner, int64_t V,
 static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
                          float temperature, int32_t top_k, float top_p, int32_t k_cap, int32_t* out_idx,
                          float* out_logit, float* out_prob, int32_t* out_count, float* out_mass, int32_t* status,
-                         const float* u, int32_t n_samples, int32_t* out_token, int32_t* out_slot, void* stream) {
+                         const float* u, int32_t n_samples, int32_t* out_token, int32_t* out_slot,
+                         void* ws, size_t ws_bytes, void* stream) {
   if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: unknown dtype %d", int(dt));
   if (rows < 0 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: bad shape rows=%lld V=%lld stride=%lld", (long long)rows, (long long)V, (long long)row_stride);
   if (V > 0x7FFFFFFF || rows > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "tslt_truncate: V and rows must fit 31 bits");
@@ -137,17 +138,20 @@ static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_
   p.out_idx = out_idx; p.out_logit = out_logit; p.out_prob = out_prob; p.out_count = out_count;
   p.out_mass = out_mass; p.status = status;
   p.u = u; p.n_samples = n_samples; p.out_token = out_token; p.out_slot = out_slot;
-  const size_t lds = plan_truncate(dt, V, p);
+  constexpr int NT = tslt::kTruncThreads;
+  const size_t lds = plan_truncate(dt, V, NT, p);
 
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   hipError_t e;
   const bool big_lds = lds + sizeof(tslt::TruncateShared) > 48 * 1024;
+  (void)ws; (void)ws_bytes;
+  const dim3 grid{unsigned(rows)}, block{unsigned(NT)};
   if (dt == TSLT_BF16) {
-    if (big_lds && (e = allow_large_lds(tslt::truncate_kernel<tslt::Bf16>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
-    hipLaunchKernelGGL(tslt::truncate_kernel<tslt::Bf16>, dim3(unsigned(rows)), dim3(tslt::kBlock), lds, s, p);
+    if (big_lds && (e = allow_large_lds(&tslt::truncate_kernel<tslt::Bf16, NT>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    hipLaunchKernelGGL((tslt::truncate_kernel<tslt::Bf16, NT>), grid, block, lds, s, p);
   } else {
-    if (big_lds && (e = allow_large_lds(tslt::truncate_kernel<float>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
-    hipLaunchKernelGGL(tslt::truncate_kernel<float>, dim3(unsigned(rows)), dim3(tslt::kBlock), lds, s, p);
+    if (big_lds && (e = allow_large_lds(&tslt::truncate_kernel<float, NT>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    hipLaunchKernelGGL((tslt::truncate_kernel<float, NT>), grid, block, lds, s, p);
   }
   if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "tslt_truncate launch");
   return TSLT_OK;
@@ -157,9 +161,8 @@ int tslt_truncate(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, in
                   float temperature, int32_t top_k, float top_p, int32_t k_cap, int32_t* out_idx,
                   float* out_logit, float* out_prob, int32_t* out_count, float* out_mass, int32_t* status,
                   void* ws, size_t ws_bytes, void* stream) {
-  (void)ws; (void)ws_bytes;
   return truncate_impl(logits, dt, rows, V, row_stride, temperature, top_k, top_p, k_cap, out_idx, out_logit, out_prob,
-                       out_count, out_mass, status, nullptr, 0, nullptr, nullptr, stream);
+                       out_count, out_mass, status, nullptr, 0, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 int tslt_truncate_sample(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
@@ -167,12 +170,11 @@ int tslt_truncate_sample(const void* logits, tslt_dtype dt, int64_t rows, int64_
                          float* out_logit, float* out_prob, int32_t* out_count, float* out_mass, int32_t* status,
                          const float* u, int32_t n_samples, int32_t* out_token, int32_t* out_slot,
                          void* ws, size_t ws_bytes, void* stream) {
-  (void)ws; (void)ws_bytes;
   if (n_samples < 1 || n_samples > TSLT_MAX_BRANCH)
     return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate_sample: n_samples must be in 1..%d", TSLT_MAX_BRANCH);
   if (rows > 0 && (!u || !out_token)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate_sample: null pointer");
   return truncate_impl(logits, dt, rows, V, row_stride, temperature, top_k, top_p, k_cap, out_idx, out_logit, out_prob,
-                       out_count, out_mass, status, u, n_samples, out_token, out_slot, stream);
+                       out_count, out_mass, status, u, n_samples, out_token, out_slot, ws, ws_bytes, stream);
 }
 
 int tslt_sample(const int32_t* idx, const float* logit, const int32_t* count, int64_t rows, int32_t k_cap,

@@ -3,12 +3,12 @@
 // Kernel A, one workgroup per (sequence, draft position): eval_row_on_set over the target row, then
 // the ratio p(x)/q_hat(x) of the draft token, the acceptance decision u < min(1, ratio) and Lemma 1's
 // sum min(p, q_hat).
-// Kernel B1, a few workgroups per sequence: finds the first rejected position j (or the bonus row)
-// from kernel A's decisions and sweeps that one target row in fp64, each workgroup a segment.
-// Kernel B2, one workgroup per sequence: inverse CDF of norm(max(0, p - q_hat)) (or of p for the bonus
-// row) from the sweep's sums, and the sequence's outputs.  (Two kernels rather than a "last workgroup
-// finishes" scheme: a device-scope fence per workgroup writes back and invalidates the L2 of the XCD,
-// which costs far more than a launch.)
+// Kernel B, one workgroup of 1024 threads per sequence: finds the first rejected position j (or the bonus
+// row) from kernel A's decisions, sweeps that one target row in fp64 with all its waves, and then, on its
+// first four waves, draws from norm(max(0, p - q_hat)) (or from p for the bonus row) by inverse CDF and
+// writes the sequence's outputs.  One workgroup per row keeps the sweep's sums in LDS; splitting a row
+// over workgroups would need a device-scope fence per workgroup, which writes back and invalidates the
+// L2 of an XCD and costs far more than it saves.
 #pragma once
 #include "rowops.h"
 
@@ -34,26 +34,17 @@ struct VerifyParams {
   // workspace
   int32_t* flags;        // [B, gamma] 1 accepted, 0 rejected, 2 row unusable
   int32_t* row_status;   // [B, gamma]
-  SegResult* segs;       // [B, n_seg + 2]
-  double* subs;          // [B, n_seg, kSubChunks] mass of every run of a segment, in the segment's units
-  int n_seg;             // body segments per row (upper bound used for the layout)
-  int n_seg_grid;        // segment groups of kernel B1 per sequence
-  int use_table;         // kernel B1 sums bf16 rows through the exp table
+  int use_table;         // kernel B sums bf16 rows through the exp table
 };
 
 inline size_t verify_workspace_bytes(int64_t B, int64_t gamma, int64_t V, int k_cap) {
-  (void)k_cap;
-  const size_t n_seg = size_t(row_segments(V));
-  return align256(size_t(B) * gamma * 4) * 2 + align256(size_t(B) * (n_seg + 2) * sizeof(SegResult)) +
-         align256(size_t(B) * n_seg * kSubChunks * sizeof(double));
+  (void)V; (void)k_cap;
+  return align256(size_t(B) * gamma * 4) * 2;
 }
 inline void verify_carve_workspace(VerifyParams& p, void* ws) {
   char* w = reinterpret_cast<char*>(ws);
-  p.n_seg = row_segments(p.V);
   p.flags = reinterpret_cast<int32_t*>(w); w += align256(size_t(p.B) * p.gamma * 4);
-  p.row_status = reinterpret_cast<int32_t*>(w); w += align256(size_t(p.B) * p.gamma * 4);
-  p.segs = reinterpret_cast<SegResult*>(w); w += align256(size_t(p.B) * (p.n_seg + 2) * sizeof(SegResult));
-  p.subs = reinterpret_cast<double*>(w);
+  p.row_status = reinterpret_cast<int32_t*>(w);
 }
 
 template <typename T> __device__ __forceinline__ const void* target_row(const VerifyParams& p, int64_t b, int j) {
@@ -114,72 +105,193 @@ __global__ __launch_bounds__(kBlock) void verify_accept_kernel(const VerifyParam
 }
 
 // ---------------------------------------------------------------------------------------------
-// Kernels B1 and B2
+// Kernel B: one workgroup of 1024 threads per sequence.  All 16 waves sweep the row to be sampled (wave
+// w takes runs w, w + 16, ...; the run and segment sums stay in LDS), then waves 4..15 end and the first
+// four do the inverse CDF (finish_core) and write the sequence's outputs.
 // ---------------------------------------------------------------------------------------------
-// First rejected position of sequence b, or gamma when every draft token was accepted (block-wide).
-__device__ __forceinline__ int first_rejection(const VerifyParams& p, int64_t b, VerifyShared& sh) {
-  const int tid = threadIdx.x;
-  int jstar = p.gamma;
-  for (int j = tid; j < p.gamma; j += kBlock)
-    if (p.flags[b * p.gamma + j] != 1) { jstar = j; break; }
-#pragma unroll
-  for (int s = 32; s > 0; s >>= 1) { const int o = __shfl_xor(jstar, s, 64); jstar = o < jstar ? o : jstar; }
-  __syncthreads();
-  if (lane_id() == 0) sh.red.i[wave_id()] = jstar;
-  __syncthreads();
-  jstar = sh.red.i[0];
-#pragma unroll
-  for (int w = 1; w < kWaves; ++w) jstar = sh.red.i[w] < jstar ? sh.red.i[w] : jstar;
-  __syncthreads();
-  return jstar;
-}
+constexpr int kResThreads = 1024;
+constexpr int kResWaves = kResThreads / 64;
+constexpr int kMaxSegs = kBlock - 2;          // finish_core handles at most kBlock pieces (segments + 2 edges)
 
-// Workgroups are persistent: each builds the exp table once (bf16 rows) and then takes the
-// (sequence, segment group) items blockIdx.x, blockIdx.x + gridDim.x, ...
 template <typename T>
-__global__ __launch_bounds__(kBlock) void verify_sweep_kernel(const VerifyParams p) {
+__global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const VerifyParams p) {
+  constexpr int E = ElemTraits<T>::kPerVec;
   __shared__ VerifyShared sh;
+  __shared__ double subs_l[kMaxSegs * kSubChunks];     // mass of every run, in its segment's units
+  __shared__ SegResult segs_l[kMaxSegs + 2];
+  __shared__ float run_max[kResWaves];
+  __shared__ int jstar_l, flags_l;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int64_t b = blockIdx.x;
+
+  // first rejected position, or gamma when every draft token was accepted
+  if (wave == 0) {
+    int j0 = p.gamma;
+    for (int j = lane; j < p.gamma; j += 64)
+      if (p.flags[b * p.gamma + j] != 1) { j0 = j; break; }
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) { const int o = __shfl_xor(j0, m, 64); j0 = o < j0 ? o : j0; }
+    if (lane == 0) { jstar_l = j0; flags_l = 0; }
+  }
   double* table = nullptr;
   if (std::is_same<T, Bf16>::value && p.use_table) {
     table = reinterpret_cast<double*>(dyn_lds);
-    build_exp_table(table, p.rT);
+    build_exp_table(table, p.rT, kResThreads);
   }
-  const int n_seg_grid = p.n_seg_grid;      // segment groups per sequence (layout bound; rows may need fewer)
-  const int64_t n_items = p.B * n_seg_grid;
-  for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
-    const int64_t b = item / n_seg_grid;
-    const int seg = int(item - b * n_seg_grid);
-    const int jstar = first_rejection(p, b, sh);
-    if (jstar < p.gamma && p.flags[b * p.gamma + jstar] == 2) continue;   // unusable row: nothing to sample
-    const void* row = target_row<T>(p, b, jstar);
-    const RowSplit rs = split_row<T>(row, p.V);
-    // a row that kernel A has accepted or rejected has been validated there; the bonus row is checked here
-    sweep_group<T>(row, rs, seg, jstar == p.gamma, p.rT, table, p.segs + size_t(b) * (p.n_seg + 2),
-                     p.subs + size_t(b) * p.n_seg * kSubChunks, sh);
-    __syncthreads();
-  }
-}
+  __syncthreads();
+  const int jstar = jstar_l;
+  const bool residual = jstar < p.gamma;
+  const bool unusable = residual && p.flags[b * p.gamma + jstar] == 2;
+  const void* row = target_row<T>(p, b, jstar);
+  const RowSplit rs = split_row<T>(row, p.V);
+  const int n_seg_row = int((rs.nvec + kSegVecsTotal - 1) / kSegVecsTotal);
+  const int n_runs = int((rs.nvec + kRunVecs - 1) / kRunVecs);
+  const bool check = !residual;     // kernel A has validated the rows it decided on; the bonus row is new
 
-template <typename T>
-__global__ __launch_bounds__(kBlock) void verify_finish_kernel(const VerifyParams p) {
-  __shared__ VerifyShared sh;
-  const int tid = threadIdx.x;
-  const int64_t b = blockIdx.x;
-  const int jstar = first_rejection(p, b, sh);
+  if (!unusable) {
+    auto load_run = [&](int run, uint4 (&q)[kSegVecs]) {
+      const int64_t vbase = int64_t(run) * kRunVecs + lane;
+#pragma unroll
+      for (int i = 0; i < kSegVecs; ++i) {
+        q[i] = neg_inf_vec<T>();
+        if (vbase + i * 64 < rs.nvec) q[i] = load_vec(&rs.body[vbase + i * 64]);
+      }
+    };
+    bool direct = true;
+    if constexpr (std::is_same<T, Bf16>::value) {
+      if (table != nullptr) {
+        int flags = 0;
+        uint4 d[kSegVecs], dn[kSegVecs];
+        if (wave < n_runs) load_run(wave, d);
+        for (int run = wave; run < n_runs; run += kResWaves) {
+          if (run + kResWaves < n_runs) load_run(run + kResWaves, dn);
+          const int64_t vbase = int64_t(run) * kRunVecs + lane;
+          double acc = 0.0;
+#pragma unroll
+          for (int i = 0; i < kSegVecs; ++i)
+            if (vbase + i * 64 < rs.nvec) acc += table_vec_sum(d[i], table, p.rT, flags);
+          const double run_sum = wave_sum_f64(acc);
+          if (lane == 0) subs_l[run] = run_sum;
+          if (run + kResWaves < n_runs) {
+#pragma unroll
+            for (int i = 0; i < kSegVecs; ++i) d[i] = dn[i];
+          }
+        }
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) flags |= __shfl_xor(flags, m, 64);
+        if (lane == 0 && flags) atomicOr(&flags_l, flags);
+        __syncthreads();
+        const int fl = flags_l;
+        direct = (fl & 2) != 0;
+        if (!direct) {
+          const int bad = (fl & 1) && check ? 1 : 0;
+          if (tid < n_seg_row) {
+            double t = 0.0;
+            for (int r = tid * kSubChunks; r < (tid + 1) * kSubChunks && r < n_runs; ++r) t += subs_l[r];
+            for (int r = n_runs; r < (tid + 1) * kSubChunks; ++r) if (r >= tid * kSubChunks) subs_l[r] = 0.0;
+            segs_l[1 + tid].sum = bad ? 0.0 : t;
+            segs_l[1 + tid].smax = (t > 0.0 && !bad) ? 0.0f : -INFINITY;
+            segs_l[1 + tid].bad = bad;
+          }
+        }
+        __syncthreads();
+      }
+    }
+    if (direct) {
+      // every term an fp64 exponential referenced to its segment's maximum; the four waves w, w+1, w+2,
+      // w+3 (w a multiple of 4) hold the four runs of one segment
+      for (int run0 = 0; run0 < n_seg_row * kSubChunks; run0 += kResWaves) {
+        const int run = run0 + wave;
+        const int seg = run / kSubChunks;
+        uint4 d[kSegVecs];
+        load_run(run, d);                       // vectors past the row's end read as -inf
+        float vmax = -INFINITY;
+        int bad = 0;
+#pragma unroll
+        for (int i = 0; i < kSegVecs; ++i) {
+          float v[E];
+          unpack<T>(d[i], v);
+#pragma unroll
+          for (int e = 0; e < E; ++e) {
+            if (check) bad |= (v[e] != v[e] || v[e] == INFINITY) ? 1 : 0;
+            vmax = fmaxf(vmax, v[e]);
+          }
+        }
+#pragma unroll
+        for (int m = 32; m > 0; m >>= 1) { vmax = fmaxf(vmax, __shfl_xor(vmax, m, 64)); bad |= __shfl_xor(bad, m, 64); }
+        if (lane == 0) { run_max[wave] = vmax; if (bad) atomicOr(&flags_l, 4); }
+        __syncthreads();
+        const int w0 = wave & ~(kSubChunks - 1);
+        float smax_v = run_max[w0];
+#pragma unroll
+        for (int k = 1; k < kSubChunks; ++k) smax_v = fmaxf(smax_v, run_max[w0 + k]);
+        const float smax = __fmul_rn(smax_v, p.rT);      // scaling is monotone
+        double acc = 0.0;
+        if (smax > -INFINITY && smax < INFINITY) {
+          const double m = double(smax);
+#pragma unroll
+          for (int i = 0; i < kSegVecs; ++i) {
+            float v[E];
+            unpack<T>(d[i], v);
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc += exp64(double(__fmul_rn(v[e], p.rT)) - m);    // -inf gives exactly 0
+          }
+        }
+        const double run_sum = wave_sum_f64(acc);
+        if (lane == 0 && seg < n_seg_row) {
+          subs_l[run] = run_sum;
+          if ((wave & (kSubChunks - 1)) == 0) segs_l[1 + seg].smax = smax;
+        }
+        __syncthreads();                          // run_max is reused by the next round
+      }
+      const int bad_row = (flags_l & 4) ? 1 : 0;
+      if (tid < n_seg_row) {
+        double t = 0.0;
+        for (int r = tid * kSubChunks; r < (tid + 1) * kSubChunks; ++r) t += subs_l[r];
+        segs_l[1 + tid].sum = bad_row ? 0.0 : t;
+        segs_l[1 + tid].bad = bad_row;
+      }
+    }
+    if (tid == 0) {
+      // the two edge pieces (at most E-1 elements each)
+      for (int piece = 0; piece < 2; ++piece) {
+        const int e0 = piece == 0 ? 0 : rs.head, e1 = piece == 0 ? rs.head : rs.head + rs.tail;
+        float smax = -INFINITY;
+        int bad = 0;
+        for (int e = e0; e < e1; ++e) {
+          const float t = load_elem<T>(row, edge_index<T>(rs, e));
+          if (t != t || t == INFINITY) bad = 1;
+          smax = fmaxf(smax, __fmul_rn(t, p.rT));
+        }
+        double sum = 0.0;
+        if (smax > -INFINITY && !bad)
+          for (int e = e0; e < e1; ++e) {
+            const float t = load_elem<T>(row, edge_index<T>(rs, e));
+            if (t > -INFINITY) sum += exp64(double(__fmul_rn(t, p.rT)) - double(smax));
+          }
+        SegResult& o = segs_l[piece == 0 ? 0 : n_seg_row + 1];
+        o.sum = sum; o.smax = smax; o.bad = bad;
+      }
+    }
+  }
+  __syncthreads();
+  if (__builtin_amdgcn_readfirstlane(wave) >= kWaves) return;     // whole waves end here
+
+  // ---- the first four waves: inverse CDF and outputs ---------------------------------------------
   int st = 0;
   for (int j = tid; j <= jstar && j < p.gamma; j += kBlock) st |= p.row_status[b * p.gamma + j];
   st = block_or_i32<kWaves>(st, sh.red);
-
   FinishArgs a;
-  a.row = target_row<T>(p, b, jstar);
-  a.rs = split_row<T>(a.row, p.V);
-  a.n_seg_row = int((a.rs.nvec + kSegVecsTotal - 1) / kSegVecsTotal);
+  a.row = row;
+  a.rs = rs;
+  a.n_seg_row = n_seg_row;
   a.V = p.V;
   a.rT = p.rT;
-  a.segs = p.segs + size_t(b) * (p.n_seg + 2);
-  a.subs = p.subs + size_t(b) * p.n_seg * kSubChunks;
-  const bool residual = jstar < p.gamma;
+  a.segs = segs_l;
+  a.subs = subs_l;
   const int64_t r = b * p.gamma + (residual ? jstar : 0);
   int count = residual ? p.q_count[r] : 0;
   a.count = count < 0 ? 0 : (count > p.k_cap ? p.k_cap : count);
@@ -187,7 +299,7 @@ __global__ __launch_bounds__(kBlock) void verify_finish_kernel(const VerifyParam
   a.ql = p.q_logit + size_t(r) * p.k_cap;
   a.stages = residual ? 1 : 0;
   a.u = p.u_resample[b * (p.gamma + 1) + jstar];
-  a.unusable = residual && p.flags[b * p.gamma + jstar] == 2;
+  a.unusable = unusable;
   const int token = finish_core<T>(a, sh, st);
 
   int32_t* ot = p.out_tokens + size_t(b) * (p.gamma + 1);
@@ -211,15 +323,8 @@ template <typename T> hipError_t launch_verify(VerifyParams p, hipStream_t s, in
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (phases & 2) {
-    const int E = ElemTraits<T>::kPerVec;
-    int n_seg = int((p.V / E + 1 + kSegVecsTotal - 1) / kSegVecsTotal);
-    if (n_seg > p.n_seg) n_seg = p.n_seg;
-    p.n_seg_grid = (n_seg + kGroupSegs - 1) / kGroupSegs;
     p.use_table = std::is_same<T, Bf16>::value && exp_table_usable(p.rT) ? 1 : 0;
-    const int64_t grid = std::min<int64_t>(p.B * p.n_seg_grid, sweep_grid_limit());
-    hipLaunchKernelGGL(verify_sweep_kernel<T>, dim3(unsigned(grid)), dim3(kBlock), p.use_table ? kTabBytes : 0, s, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(verify_finish_kernel<T>, dim3(unsigned(p.B)), dim3(kBlock), 0, s, p);
+    hipLaunchKernelGGL(verify_resample_kernel<T>, dim3(unsigned(p.B)), dim3(kResThreads), p.use_table ? kTabBytes : 0, s, p);
     e = hipGetLastError();
   }
   return e;
