@@ -462,12 +462,38 @@ struct FinishArgs {
   int unusable;             // the row is known to be unusable: no token
 };
 
+// The set's entries as finish_core needs them, one slot per (thread, k): token index (-1 if unused or out
+// of range), received scaled logit, raw target logit at that index.  A caller with other work to do first
+// (a sweep) can load them early, so that the dependent loads travel meanwhile.
+struct SetEntries {
+  int yi[kSetPer];
+  float ql[kSetPer];
+  float tv[kSetPer];
+  float ql0;
+};
+template <typename T>
+__device__ __forceinline__ void load_set_entries(const void* row, int64_t V, const int32_t* qi, const float* ql,
+                                                 int count, SetEntries& se) {
+  const int tid = threadIdx.x;
+  se.ql0 = count > 0 ? ql[0] : 0.0f;
+#pragma unroll
+  for (int k = 0; k < kSetPer; ++k) {
+    const int i = tid + k * kBlock;
+    se.yi[k] = -1; se.ql[k] = 0.0f; se.tv[k] = -INFINITY;
+    if (i < count) {
+      se.ql[k] = ql[i];
+      const int y = qi[i];
+      if (y >= 0 && y < V) { se.yi[k] = y; se.tv[k] = load_elem<T>(row, y); }
+    }
+  }
+}
+
 // Returns the token (-1 if none) and ORs TSLT_ROW_* bits into st.  After m updates with the same q_hat
 // the distribution is c * p outside the set and a_i on it, where a and c follow the recursion
 // a <- max(0, a - q_hat) / Z, c <- c / Z, Z = sum(max(0, a - q_hat)) + c * p_out; in units of the row's
 // unnormalised terms e_y that is e_y outside the set and a_i * z_p / c on it.
 template <typename T>
-__device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st) {
+__device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const SetEntries* pre = nullptr) {
   constexpr int E = ElemTraits<T>::kPerVec;
   constexpr int kMaxPer = kSetPer;
   constexpr int kRun = kRunVecs * E;        // elements in a run
@@ -507,9 +533,10 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st) {
     // a_i * z_p / c instead of e_i
     const int stages = a.stages;
     int count = stages > 0 ? a.count : 0;
-    const int32_t* qi = a.qi;
-    const float* ql = a.ql;
-    const double ql0 = count > 0 ? double(ql[0]) : 0.0;
+    SetEntries se_local;
+    if (pre == nullptr) load_set_entries<T>(row, a.V, a.qi, a.ql, count, se_local);
+    const SetEntries& se = pre ? *pre : se_local;
+    const double ql0 = double(se.ql0);
     double w64[kMaxPer], corr[kMaxPer], e_s[kMaxPer];
     int yi[kMaxPer];
     double sum_w = 0.0, sum_e = 0.0;
@@ -518,12 +545,11 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st) {
       const int i = tid + k * kBlock;
       w64[k] = 0.0; corr[k] = 0.0; e_s[k] = 0.0; yi[k] = -1;
       if (i < count) {
-        w64[k] = exp64(double(ql[i]) - ql0);
+        w64[k] = exp64(double(se.ql[k]) - ql0);
         sum_w += w64[k];
-        const int y = qi[i];
-        if (y >= 0 && y < a.V) {
-          yi[k] = y;
-          const float t = load_elem<T>(row, y);
+        if (se.yi[k] >= 0) {
+          yi[k] = se.yi[k];
+          const float t = se.tv[k];
           e_s[k] = t > -INFINITY ? exp64(double(__fmul_rn(t, rT)) - double(smax)) : 0.0;
           sum_e += e_s[k];
         }

@@ -150,6 +150,19 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
   const int n_seg_row = int((rs.nvec + kSegVecsTotal - 1) / kSegVecsTotal);
   const int n_runs = int((rs.nvec + kRunVecs - 1) / kRunVecs);
   const bool check = !residual;     // kernel A has validated the rows it decided on; the bonus row is new
+  // what the first four waves need after the sweep is requested now: status words, the uniform, and the
+  // set's entries with the target logits at their indices (three dependent loads)
+  const int64_t r = b * p.gamma + (residual ? jstar : 0);
+  int st = 0, count = 0;
+  float u_res = 0.0f;
+  SetEntries se;
+  if (wave < kWaves) {
+    for (int j = tid; j <= jstar && j < p.gamma; j += kBlock) st |= p.row_status[b * p.gamma + j];
+    u_res = p.u_resample[b * (p.gamma + 1) + jstar];
+    count = residual ? p.q_count[r] : 0;
+    count = count < 0 ? 0 : (count > p.k_cap ? p.k_cap : count);
+    load_set_entries<T>(row, p.V, p.q_idx + size_t(r) * p.k_cap, p.q_logit + size_t(r) * p.k_cap, count, se);
+  }
 
   if (!unusable) {
     auto load_run = [&](int run, uint4 (&q)[kSegVecs]) {
@@ -281,8 +294,6 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
   if (__builtin_amdgcn_readfirstlane(wave) >= kWaves) return;     // whole waves end here
 
   // ---- the first four waves: inverse CDF and outputs ---------------------------------------------
-  int st = 0;
-  for (int j = tid; j <= jstar && j < p.gamma; j += kBlock) st |= p.row_status[b * p.gamma + j];
   st = block_or_i32<kWaves>(st, sh.red);
   FinishArgs a;
   a.row = row;
@@ -292,15 +303,13 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
   a.rT = p.rT;
   a.segs = segs_l;
   a.subs = subs_l;
-  const int64_t r = b * p.gamma + (residual ? jstar : 0);
-  int count = residual ? p.q_count[r] : 0;
-  a.count = count < 0 ? 0 : (count > p.k_cap ? p.k_cap : count);
+  a.count = count;
   a.qi = p.q_idx + size_t(r) * p.k_cap;
   a.ql = p.q_logit + size_t(r) * p.k_cap;
   a.stages = residual ? 1 : 0;
-  a.u = p.u_resample[b * (p.gamma + 1) + jstar];
+  a.u = u_res;
   a.unusable = unusable;
-  const int token = finish_core<T>(a, sh, st);
+  const int token = finish_core<T>(a, sh, st, &se);
 
   int32_t* ot = p.out_tokens + size_t(b) * (p.gamma + 1);
   for (int j = tid; j <= p.gamma; j += kBlock) {
