@@ -322,19 +322,28 @@ def verify_chain(target, T, q_idx, q_logit, q_count, tokens, u_accept, u_resampl
 # ----------------------------------------------------------------------------------------------
 # Algorithm 5: multi-candidate verification at one node
 # ----------------------------------------------------------------------------------------------
-def mcveri(p, q_idx, q_prob, cands, u_accept, u_resample) -> dict:
+def mcveri(p, q_idx, q_prob, cands, u_accept, u_resample, without_replacement: bool = False) -> dict:
     """p: dense fp64 target distribution of the node; (q_idx, q_prob): sparse q_hat; cands[k]
     candidate tokens (-1 = absent); u_accept[k]; u_resample scalar.
-    P^(1) = P; candidate i is accepted iff u_i < min(1, p^(i)(x_i)/q_hat(x_i)); otherwise
-    p^(i+1) = norm(max(0, p^(i) - q_hat)) with the same q_hat at every step; after k rejections
-    the output is a sample of P^(k+1).  Returns token, slot (accepted candidate number or -1),
-    ratios, accept margins, the cdf margin, the stage acceptance rates beta^(i) =
-    sum_x min(q_hat, p^(i)) met on the way, and per candidate the factor prod_{j<i} 1/Z_j by which an
-    error in p is magnified in p^(i) (Z_j = sum_x max(0, p^(j) - q_hat) <= 1 is the normaliser of update j)."""
+    P^(1) = P; candidate i is accepted iff u_i < min(1, p^(i)(x_i)/q^(i)(x_i)); otherwise
+    p^(i+1) = norm(max(0, p^(i) - q^(i))); after k rejections the output is a sample of P^(k+1).
+
+    without_replacement = False is Algorithm 5 as printed: q^(i) = q_hat at every step, exact when the
+    candidates are i.i.d. draws from q_hat (Algorithm 4).
+    without_replacement = True is the rule for candidates drawn one after the other from q_hat without
+    replacement (the direction Section 4.2 only cites): candidate i was drawn from q^(i) = q_hat with
+    x_1..x_{i-1} removed and the rest renormalised, so stage i is single-candidate speculative sampling
+    with target p^(i) and THAT proposal, which keeps the output distributed as P.
+
+    Returns token, slot (accepted candidate number or -1), ratios, accept margins, the cdf margin, the
+    stage acceptance rates beta^(i) = sum_x min(q^(i), p^(i)) met on the way, and per candidate the factor
+    prod_{j<i} 1/Z_j by which an error in p is magnified in p^(i) (Z_j = sum_x max(0, p^(j) - q^(j)) <= 1 is
+    the normaliser of update j)."""
     p_i = np.asarray(p, dtype=np.float64).copy()
     V = p_i.shape[0]
     ids = np.asarray(q_idx, dtype=np.int64)
-    q_dense = scatter_sparse(V, ids, q_prob)
+    q_hat = scatter_sparse(V, ids, q_prob)
+    q_i = q_hat.copy()                      # proposal of the current stage
     k = len(cands)
     ratio = np.full(k, np.nan)
     margin = np.full(k, np.inf)
@@ -347,13 +356,13 @@ def mcveri(p, q_idx, q_prob, cands, u_accept, u_resample) -> dict:
         if x < 0:
             continue
         amp[i] = gain
-        betas.append(float(np.sum(np.minimum(q_dense, p_i))))
-        if q_dense[x] <= 0.0:
+        betas.append(float(np.sum(np.minimum(q_i, p_i))))
+        if q_i[x] <= 0.0:                   # not in the set (or, without replacement, drawn before)
             status |= STATUS_TOKEN_NOT_IN_SET
             ratio[i] = -1.0
             accepted = False
         else:
-            ratio[i] = p_i[x] / q_dense[x]
+            ratio[i] = p_i[x] / q_i[x]
             bound = min(1.0, ratio[i])
             ui = np.float64(np.float32(u_accept[i]))
             accepted = bool(ui < bound)
@@ -361,11 +370,15 @@ def mcveri(p, q_idx, q_prob, cands, u_accept, u_resample) -> dict:
         if accepted:
             return dict(token=x, slot=i, ratio=ratio, accept_margin=margin, cdf_margin=np.inf,
                         betas=betas, status=status, amp=amp)
-        r = np.maximum(0.0, p_i - q_dense)
+        r = np.maximum(0.0, p_i - q_i)
         Zr = np.sum(r)
         if Zr > 0.0:                        # always true after a rejection in exact arithmetic
             p_i = r / Zr
             gain /= Zr
+        if without_replacement and q_hat[x] > 0.0:
+            q_hat[x] = 0.0                  # x leaves the urn; the next candidate came from what is left
+            rest = np.sum(q_hat)
+            q_i = q_hat / rest if rest > 0.0 else q_hat.copy()
     y, mg = inverse_cdf(p_i, u_resample)
     return dict(token=y, slot=-1, ratio=ratio, accept_margin=margin, cdf_margin=mg, betas=betas,
                 status=status, amp=amp)
@@ -396,7 +409,7 @@ def child_node(layout, expansion, node: int, slot: int) -> int:
 
 
 def verify_tree_seq(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, u_accept,
-                    u_resample) -> dict:
+                    u_resample, without_replacement: bool = False) -> dict:
     """target [N_nodes, V]; sparse sets [N_int, k_cap]; cand_tokens, u_accept [N_nodes-1] (entry
     n-1 belongs to node n); u_resample [N_nodes].  Runs Algorithm 5 at every non-leaf node, draws a
     target sample at every leaf, then walks from the root through accepted children."""
@@ -423,7 +436,7 @@ def verify_tree_seq(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, 
             cnt = int(q_count[n])
             qh = sparse_probs(q_logit[n], cnt)
             r = mcveri(p, q_idx[n][:cnt], qh, cand_tokens[c0 - 1:c0 - 1 + k], u_accept[c0 - 1:c0 - 1 + k],
-                       u_resample[n])
+                       u_resample[n], without_replacement)
             node_token[n], node_slot[n] = r["token"], r["slot"]
             ratio[c0 - 1:c0 - 1 + k] = r["ratio"]
             acc_margin[c0 - 1:c0 - 1 + k] = r["accept_margin"]
@@ -448,7 +461,8 @@ def verify_tree_seq(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, 
                 accept_margin=acc_margin, amp=amp, cdf_margin=cdf_margin, status=status)
 
 
-def verify_tree(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, u_accept, u_resample) -> dict:
+def verify_tree(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, u_accept, u_resample,
+                without_replacement: bool = False) -> dict:
     """verify_tree_seq over a batch (leading dimension B on every array)."""
     target = np.asarray(target)
     B = target.shape[0]
@@ -461,7 +475,7 @@ def verify_tree(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, u_ac
                cdf_margin=np.full((B, lay["n_nodes"]), np.inf), status=np.zeros(B, np.int32), path=[])
     for b in range(B):
         r = verify_tree_seq(target[b], T, expansion, q_idx[b], q_logit[b], q_count[b], cand_tokens[b],
-                            u_accept[b], u_resample[b])
+                            u_accept[b], u_resample[b], without_replacement)
         for k in ("node_token", "node_slot", "seq", "ratio", "accept_margin", "amp", "cdf_margin"):
             out[k][b] = r[k]
         out["len"][b] = r["len"]

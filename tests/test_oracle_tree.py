@@ -1,7 +1,8 @@
 """Pins for the oracle's multi-candidate verification (Algorithm 5) and token-tree verification
 (Algorithm 8), no GPU: losslessness for i.i.d. candidates by exhaustive enumeration of candidate
-tuples at V <= 8, the stage acceptance rates beta^(j) and the total rate theta of Section 4.3, the
-tree identities of Section 4.1, and reductions to Algorithm 3.
+tuples at V <= 8 (and, for candidates drawn without replacement, of the rule with renormalised stage
+proposals), the stage acceptance rates beta^(j) and the total rate theta of Section 4.3, the tree
+identities of Section 4.1, and reductions to Algorithm 3.
 """
 import itertools
 
@@ -85,6 +86,88 @@ def test_mcveri_output_distribution_is_p_for_iid_candidates(V, K, k):
     assert abs(stage_acc.sum() - theta) < 1e-12
     # multi-candidate acceptance beats single-candidate (Section 5.2's observation, exact here)
     assert theta >= betas[0] - 1e-15
+
+
+def mcveri_output_distribution(p, tr, qs, tuples_with_weights, k, V, without_replacement, nr=1500):
+    """Output distribution of O.mcveri over the given weighted candidate tuples: the accept branches are
+    integrated analytically from the reported ratios, the all-rejected branch over a grid of u_resample."""
+    gr = (np.arange(nr) + 0.5) / nr
+    out = np.zeros(V)
+    for cands, w in tuples_with_weights:
+        probe = O.mcveri(p, tr["idx"], qs, cands, [0.99999994] * k, 0.5, without_replacement)
+        a = np.minimum(1.0, np.where(np.isnan(probe["ratio"]), 1.0, probe["ratio"]))
+        reach = 1.0
+        for j in range(k):
+            if np.isnan(probe["ratio"][j]):
+                break
+            out[cands[j]] += w * reach * a[j]
+            reach *= (1 - a[j])
+            if reach == 0:
+                break
+        if reach > 0:
+            res = np.zeros(V)
+            for ur in gr:
+                r = O.mcveri(p, tr["idx"], qs, cands, [0.99999994] * k, ur, without_replacement)
+                assert r["slot"] == -1 and r["token"] not in cands
+                res[r["token"]] += 1
+            out += w * reach * res / nr
+    return out
+
+
+@pytest.mark.parametrize("V,K,k", [(6, 3, 2), (8, 4, 3), (7, 5, 2), (5, 3, 3)])
+def test_mcveri_without_replacement_rule_is_lossless_and_the_printed_rule_is_not(V, K, k):
+    """Candidates drawn one after the other without replacement (every ordered k-tuple of distinct tokens of
+    the set, weight prod_i q_hat(x_i) / (1 - sum_{j<i} q_hat(x_j))): with the proposal of every stage
+    renormalised over what is left the output is distributed as P; Algorithm 5 as printed (q_hat at every
+    stage) is exact only for i.i.d. candidates and misses P on these."""
+    t, tr, p, qh, qs = case(70 + V + k, V, K)
+    nr = 1500
+    tuples = []
+    for tup in itertools.permutations(range(K), k):
+        w, left = 1.0, 1.0
+        for s in tup:
+            w *= qs[s] / left
+            left -= qs[s]
+        tuples.append(([int(tr["idx"][s]) for s in tup], w))
+    assert abs(sum(w for _, w in tuples) - 1.0) < 1e-12
+    exact = mcveri_output_distribution(p, tr, qs, tuples, k, V, True, nr)
+    np.testing.assert_allclose(exact, p, atol=2.0 / nr * V)
+    # a target that is far below q_hat on the likeliest token of the set and just above it on the others:
+    # after the first rejection those others are over-proposed, later stages still reject, and there the
+    # two rules part
+    top = int(np.argmax(qs))
+    p_c = np.zeros(V)
+    p_c[tr["idx"]] = 1.1 * qs
+    p_c[tr["idx"][top]] = 0.2 * qs[top]
+    off = np.setdiff1d(np.arange(V), tr["idx"])
+    assert p_c.sum() < 1.0 and len(off) > 0
+    p_c[off] = (1.0 - p_c.sum()) / len(off)
+    exact_c = mcveri_output_distribution(p_c, tr, qs, tuples, k, V, True, nr)
+    np.testing.assert_allclose(exact_c, p_c, atol=2.0 / nr * V)
+    printed = mcveri_output_distribution(p_c, tr, qs, tuples, k, V, False, nr)
+    assert np.abs(printed - p_c).max() > 0.01 > 2 * np.abs(exact_c - p_c).max()
+    # the first stage is the same in both rules, and a single candidate makes them identical
+    c0 = [tuples[0][0][0]]
+    for u in (0.1, 0.6, 0.99):
+        a = O.mcveri(p, tr["idx"], qs, c0, [u], 0.3, True)
+        b = O.mcveri(p, tr["idx"], qs, c0, [u], 0.3, False)
+        assert a["token"] == b["token"] and a["slot"] == b["slot"] and a["ratio"][0] == b["ratio"][0]
+
+
+def test_mcveri_without_replacement_stage_proposal():
+    """Stage 2's ratio uses q_hat renormalised without the first candidate: p^(2)(x2) / (q_hat(x2) / (1 - q_hat(x1)))."""
+    V, K = 9, 4
+    t, tr, p, qh, qs = case(3, V, K)
+    order = np.argsort(p[tr["idx"]] / qs)            # most over-proposed first: certainly rejectable
+    x1, x2 = int(tr["idx"][order[0]]), int(tr["idx"][order[1]])
+    r = O.mcveri(p, tr["idx"], qs, [x1, x2], [0.99999994, 0.99999994], 0.5, True)
+    p2 = residual_dist(p, qh)
+    q2 = qh.copy(); q2[x1] = 0.0; q2 /= q2.sum()
+    assert abs(r["ratio"][1] - p2[x2] / q2[x2]) < 1e-14
+    assert abs(r["betas"][1] - np.minimum(q2, p2).sum()) < 1e-14
+    # a candidate that was drawn before cannot be drawn again: flagged and rejected
+    d = O.mcveri(p, tr["idx"], qs, [x1, x1], [0.99999994, 0.0], 0.5, True)
+    assert d["status"] & O.STATUS_TOKEN_NOT_IN_SET and d["slot"] == -1 and d["ratio"][1] == -1.0
 
 
 def test_mcveri_reports_stage_betas_and_duplicates_are_rejected():
