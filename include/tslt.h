@@ -197,9 +197,16 @@ int tslt_verify_resample(const void* target_logits, tslt_dtype dt, int64_t B, in
  *   cand_tokens   [B, N_nodes-1] int32: entry n-1 is the token of node n (n >= 1); -1 = absent
  *   u_accept      [B, N_nodes-1] fp32 one uniform per candidate node (entry n-1 for node n)
  *   u_resample    [B, N_nodes] fp32 one uniform per node
+ *   without_replacement  how the candidates of a node were drawn, which fixes the proposal q^(i) of stage i:
+ *                 0: i.i.d. from q_hat (Algorithm 4) -- q^(i) = q_hat at every stage, Algorithm 5 as printed;
+ *                 1: one after the other without replacement -- q^(i) = q_hat with the earlier candidates
+ *                 removed and the rest renormalised (each stage is single-candidate speculative sampling
+ *                 against that proposal, which keeps the output distributed as P; Section 4.2 only cites
+ *                 this direction).  Candidate i is accepted iff u < min(1, p^(i)(x_i) / q^(i)(x_i)), else
+ *                 p^(i+1) = norm(max(0, p^(i) - q^(i)))
  *   out_node_token, out_node_slot [B, N_nodes] int32: output of every node -- for a non-leaf node the
  *                 accepted candidate and its child number 0..k-1, or, after k rejections, a sample of
- *                 P^(k+1) (p^(i+1) = norm(max(0, p^(i) - q_hat)), same q_hat at every step) and -1;
+ *                 P^(k+1) and -1;
  *                 for a leaf a sample of its target distribution and -1.  Both may be NULL: then only
  *                 the nodes on the verified path are evaluated.
  *   out_seq       [B, depth+1] int32 verified sequence: walk from the root, append the node's output,
@@ -216,6 +223,7 @@ int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_
                      float target_temperature, int32_t depth, const int32_t* expansion,
                      const int32_t* q_idx, const float* q_logit, const int32_t* q_count, int32_t k_cap,
                      const int32_t* cand_tokens, const float* u_accept, const float* u_resample,
+                     int32_t without_replacement,
                      int32_t* out_node_token, int32_t* out_node_slot, int32_t* out_seq, int32_t* out_len,
                      float* out_ratio, int32_t* status, void* ws, size_t ws_bytes, void* stream);
 

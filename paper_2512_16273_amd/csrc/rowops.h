@@ -458,6 +458,9 @@ struct FinishArgs {
   const float* ql;
   int count;
   int stages;               // residual updates p <- norm(max(0, p - q_hat)) to apply; 0 samples p itself
+  const int32_t* cands;     // candidates drawn without replacement: the tokens that were tested, in order
+  int n_cands;              //   (-1 = absent); after update i the i-th of them leaves q_hat, which is
+                            //   renormalised.  Null: the same q_hat at every update
   float u;
   int unusable;             // the row is known to be unusable: no token
 };
@@ -564,11 +567,14 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const
       for (int k = 0; k < kMaxPer; ++k) { av[k] = e_s[k] / zp; w64[k] = w64[k] / sum_w; }
       const double p_out = 1.0 - sum_e / zp;
       double c = 1.0;
+      const int32_t* cands = a.cands;
+      int ci = 0;
+      double qscale = 1.0, removed = 0.0;       // the update's proposal is w64 * qscale
       for (int sgi = 0; sgi < stages; ++sgi) {
         double part = 0.0;
 #pragma unroll
         for (int k = 0; k < kMaxPer; ++k) {
-          const double d = av[k] - w64[k];
+          const double d = av[k] - w64[k] * qscale;
           av[k] = (yi[k] >= 0 && d > 0.0) ? d : 0.0;
           part += av[k];
         }
@@ -577,6 +583,21 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const
 #pragma unroll
           for (int k = 0; k < kMaxPer; ++k) av[k] /= Zs;
           c /= Zs;
+        }
+        if (cands != nullptr) {
+          // the candidate that this update rejected leaves the urn
+          int x = -1;
+          while (ci < a.n_cands && (x = cands[ci]) < 0) ++ci;
+          ++ci;
+          if (tid == 0) sh.bcast_d[2] = 0.0;
+          __syncthreads();
+#pragma unroll
+          for (int k = 0; k < kMaxPer; ++k)
+            if (x >= 0 && yi[k] == x && w64[k] > 0.0) { sh.bcast_d[2] = w64[k]; w64[k] = 0.0; }
+          __syncthreads();
+          removed += sh.bcast_d[2];
+          const double rest = 1.0 - removed;
+          qscale = rest > 0.0 ? 1.0 / rest : 0.0;
         }
       }
 #pragma unroll

@@ -31,6 +31,7 @@ struct TreeParams {
   const float* q_logit;
   const int32_t* q_count;
   int k_cap;
+  int wor;                // candidates were drawn without replacement: stage proposals are renormalised
   const int32_t* cand_tokens;
   const float* u_accept;
   const float* u_resample;
@@ -119,27 +120,34 @@ __global__ __launch_bounds__(kBlock) void tree_mcveri_kernel(const TreeParams p)
   int accepted = -1, stages = 0;
   if (ok) {
     double c = 1.0;
+    double qscale = 1.0, removed = 0.0;       // the stage's proposal is q_s * qscale
     for (int i = 0; i < k; ++i) {
       const int x = cand[i];
       if (x < 0) continue;                                      // absent candidate (block-uniform)
-      if (tid == 0) { sh.bcast_d[0] = -1.0; sh.bcast_i[0] = 0; }
+      if (tid == 0) { sh.bcast_d[0] = -1.0; sh.bcast_d[1] = 0.0; sh.bcast_i[0] = 0; }
       __syncthreads();
+      int mine = -1;
 #pragma unroll
       for (int q = 0; q < kSetPer; ++q)
-        if (yi[q] == x && q_s[q] > 0.0 && atomicCAS(&sh.bcast_i[0], 0, 1) == 0) sh.bcast_d[0] = a_s[q] / q_s[q];
+        if (yi[q] == x && q_s[q] > 0.0 && atomicCAS(&sh.bcast_i[0], 0, 1) == 0) {
+          sh.bcast_d[0] = a_s[q] / (q_s[q] * qscale);
+          sh.bcast_d[1] = q_s[q];
+          mine = q;
+        }
       __syncthreads();
       const double ratio = sh.bcast_d[0];
+      const double q_x = sh.bcast_d[1];
       const bool found = sh.bcast_i[0] != 0;
       __syncthreads();
       if (!found) st |= 4;
       if (ratio_out && tid == 0) ratio_out[i] = float(ratio);
       const double bound = ratio < 1.0 ? ratio : 1.0;
       if (found && double(u_acc[i]) < bound) { accepted = i; break; }
-      // rejected: p <- norm(max(0, p - q_hat)), the same q_hat at every step
+      // rejected: p <- norm(max(0, p - q)), q the proposal of this stage
       double part = 0.0;
 #pragma unroll
       for (int q = 0; q < kSetPer; ++q) {
-        const double d = a_s[q] - q_s[q];
+        const double d = a_s[q] - q_s[q] * qscale;
         a_s[q] = (yi[q] >= 0 && d > 0.0) ? d : 0.0;
         part += a_s[q];
       }
@@ -148,6 +156,15 @@ __global__ __launch_bounds__(kBlock) void tree_mcveri_kernel(const TreeParams p)
 #pragma unroll
         for (int q = 0; q < kSetPer; ++q) a_s[q] /= Z;
         c /= Z;
+      }
+      if (p.wor && found) {
+        // drawn without replacement: x leaves the urn and what is left is renormalised
+#pragma unroll
+        for (int q = 0; q < kSetPer; ++q)
+          if (q == mine) q_s[q] = 0.0;
+        removed += q_x;
+        const double rest = 1.0 - removed;
+        qscale = rest > 0.0 ? 1.0 / rest : 0.0;
       }
       ++stages;
     }
@@ -245,6 +262,13 @@ __global__ __launch_bounds__(kBlock) void tree_finish_kernel(const TreeParams p)
     a.qi = p.q_idx + size_t(r) * p.k_cap;
     a.ql = p.q_logit + size_t(r) * p.k_cap;
     a.stages = leaf ? 0 : p.node_stages[r];
+    a.cands = nullptr;
+    a.n_cands = 0;
+    if (!leaf && p.wor) {
+      const int layer = tree_layer(p, node);
+      a.cands = p.cand_tokens + size_t(b) * (p.n_nodes - 1) + (tree_first_child(p, node, layer) - 1);
+      a.n_cands = p.expansion[layer];
+    }
     a.u = p.u_resample[size_t(b) * p.n_nodes + node];
     a.unusable = state == 2;
     token = finish_core<T>(a, sh, st);

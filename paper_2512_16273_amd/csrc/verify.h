@@ -307,6 +307,8 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
   a.qi = p.q_idx + size_t(r) * p.k_cap;
   a.ql = p.q_logit + size_t(r) * p.k_cap;
   a.stages = residual ? 1 : 0;
+  a.cands = nullptr;
+  a.n_cands = 0;
   a.u = u_res;
   a.unusable = unusable;
   const int token = finish_core<T>(a, sh, st, &se);

@@ -61,7 +61,7 @@ def load(path: Optional[str] = None):
         fn.argtypes = [vp, c.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tslt_verify_tree.restype = c.c_int
     lib.tslt_verify_tree.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, c.POINTER(i32), vp, vp, vp, i32, vp, vp,
-                                     vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+                                     vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -213,10 +213,11 @@ def verify(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logi
 def verify_tree(target: torch.Tensor, temperature: float, expansion: Sequence[int], q_idx: torch.Tensor,
                 q_logit: torch.Tensor, q_count: torch.Tensor, cand_tokens: torch.Tensor, u_accept: torch.Tensor,
                 u_resample: torch.Tensor, all_nodes: bool = True, out: Optional[dict] = None,
-                workspace: Optional[torch.Tensor] = None) -> dict:
+                workspace: Optional[torch.Tensor] = None, without_replacement: bool = False) -> dict:
     """tslt_verify_tree: target [B, N_nodes, V]; sparse sets [B, N_int, k_cap]; cand_tokens, u_accept
     [B, N_nodes-1]; u_resample [B, N_nodes].  Returns seq [B, depth+1], len [B], node_token / node_slot
-    [B, N_nodes] (when all_nodes), ratio [B, N_nodes-1], status [B]."""
+    [B, N_nodes] (when all_nodes), ratio [B, N_nodes-1], status [B].  without_replacement selects the rule
+    for candidates that were drawn without replacement."""
     lib = load()
     _dev(target, name="target")
     if target.dim() != 3:
@@ -240,7 +241,8 @@ def verify_tree(target: torch.Tensor, temperature: float, expansion: Sequence[in
     exp_arr = (ctypes.c_int32 * depth)(*[int(k) for k in expansion])
     _check(lib.tslt_verify_tree(_ptr(target), _dtype_code(target), B, V, target.stride(1), float(temperature), depth,
                                 exp_arr, _ptr(q_idx), _ptr(q_logit), _ptr(q_count), k_cap, _ptr(cand_tokens),
-                                _ptr(u_accept), _ptr(u_resample), _ptr(out.get("node_token")),
+                                _ptr(u_accept), _ptr(u_resample), 1 if without_replacement else 0,
+                                _ptr(out.get("node_token")),
                                 _ptr(out.get("node_slot")), _ptr(out["seq"]), _ptr(out["len"]), _ptr(out.get("ratio")),
                                 _ptr(out.get("status")), _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
     return out

@@ -96,10 +96,12 @@ def oracle_chain(draft_rows, target_rows, T, top_k, top_p, k_cap, u_sample, u_ac
 
 
 def oracle_tree(draft_rows, target_rows, T, top_k, top_p, k_cap, expansion, u_sample, u_accept, u_resample,
-                without_replacement):
+                without_replacement, renormalised_rule=False):
     """The whole multi-candidate round on the host (Algorithms 7's sampling and 8): truncate every non-leaf
     node's draft row, draw its k candidates, verify the tree.  draft_rows [B, N_int, V], target_rows
-    [B, N_nodes, V] fp32 numpy; u_sample [B, N_int, k_max]."""
+    [B, N_nodes, V] fp32 numpy; u_sample [B, N_int, k_max].  without_replacement says how the candidates are
+    drawn, renormalised_rule which verification rule is applied (the printed one, or the one for candidates
+    drawn without replacement)."""
     B, n_int, V = draft_rows.shape
     lay = O.tree_layout(expansion)
     n_nodes = lay["n_nodes"]
@@ -117,7 +119,7 @@ def oracle_tree(draft_rows, target_rows, T, top_k, top_p, k_cap, expansion, u_sa
             ok = slots >= 0
             cands[b, c0 - 1:c0 - 1 + k][ok] = q_idx[b, n][slots[ok]]
     ver = O.verify_tree(target_rows, T, expansion, q_idx, q_logit, q_count, cands, np.asarray(u_accept),
-                        np.asarray(u_resample))
+                        np.asarray(u_resample), renormalised_rule)
     return dict(trunc=tr, q_idx=q_idx, q_logit=q_logit, q_count=q_count, cands=cands, verify=ver, layout=lay)
 
 

@@ -15,16 +15,16 @@ def t32(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
-def run_tree(tslt, w, tree, ref, all_nodes=True):
+def run_tree(tslt, w, tree, ref, all_nodes=True, renormalised_rule=False):
     return tslt.verify_tree(tree["target"], w.T, w.expansion, t32(ref["q_idx"]), t32(ref["q_logit"]),
                             t32(ref["q_count"]), t32(ref["cands"]), tree["u_accept"], tree["u_resample"],
-                            all_nodes=all_nodes)
+                            all_nodes=all_nodes, without_replacement=renormalised_rule)
 
 
-def oracle_for(w, tree):
+def oracle_for(w, tree, renormalised_rule=False):
     return P.oracle_tree(P.to_np(tree["draft"]), P.to_np(tree["target"]), w.T, w.top_k, w.top_p, w.k_cap, w.expansion,
                          P.to_np(tree["u_sample"]), P.to_np(tree["u_accept"]), P.to_np(tree["u_resample"]),
-                         w.without_replacement)
+                         w.without_replacement, renormalised_rule)
 
 
 @pytest.mark.parametrize("name,kw", [
@@ -45,6 +45,32 @@ def test_tree_matches_oracle(tslt, name, kw):
     torch.cuda.synchronize()
     assert torch.equal(path_only["seq"], out["seq"]) and torch.equal(path_only["len"], out["len"])
     print(name, res, "len histogram", np.bincount(ref["verify"]["len"], minlength=len(w.expansion) + 2))
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("f32-332", dict(B=3, V=5003, expansion=(3, 3, 2), top_k=8, k_cap=8)),
+    ("bf16-44", dict(B=2, V=20011, dtype="bf16", expansion=(4, 4), top_k=32, k_cap=32, T=0.9)),
+    ("bf16-noisy", dict(B=3, V=9000, dtype="bf16", expansion=(4, 3), top_k=6, k_cap=8, noise_t=2.5)),
+    ("f32-exhaust", dict(B=2, V=3000, expansion=(4, 4), top_k=3, k_cap=4)),       # more candidates than set entries
+])
+def test_tree_rule_for_candidates_drawn_without_replacement(tslt, name, kw):
+    """The rule with renormalised stage proposals, on candidates drawn without replacement; it must differ
+    from the printed rule somewhere (else the flag could be ignored unnoticed)."""
+    w = W.scaled(W.WORKLOADS["tree"], without_replacement=True, **kw)
+    tree = W.make_tree(w, 7, DEV)
+    ref = oracle_for(w, tree, renormalised_rule=True)
+    out = run_tree(tslt, w, tree, ref, all_nodes=True, renormalised_rule=True)
+    torch.cuda.synchronize()
+    res = P.compare_tree(out, ref, w.expansion, all_nodes=True, label=name)
+    path_only = run_tree(tslt, w, tree, ref, all_nodes=False, renormalised_rule=True)
+    printed = run_tree(tslt, w, tree, ref, all_nodes=True, renormalised_rule=False)
+    torch.cuda.synchronize()
+    assert torch.equal(path_only["seq"], out["seq"]) and torch.equal(path_only["len"], out["len"])
+    r_new, r_old = P.to_np(out["ratio"]), P.to_np(printed["ratio"])
+    both = ~np.isnan(r_new) & ~np.isnan(r_old)
+    differ = int(np.count_nonzero(np.abs(r_new[both] - r_old[both]) > 1e-3 * np.abs(r_old[both])))
+    print(name, res, "ratios that differ between the rules:", differ)
+    assert differ > 0 or name == "f32-exhaust"      # (there every later ratio is 0 under both rules)
 
 
 def test_unary_tree_equals_chain_verify(tslt):
@@ -121,3 +147,10 @@ def test_tree_config_shape_few_trees(tslt):
     out = run_tree(tslt, w, tree, ref)
     torch.cuda.synchronize()
     print(P.compare_tree(out, ref, w.expansion, label="config4"), "lens", ref["verify"]["len"])
+    # the same trees under the rule that is exact for candidates drawn this way
+    ref["verify"] = O.verify_tree(P.to_np(tree["target"]), w.T, w.expansion, ref["q_idx"], ref["q_logit"], ref["q_count"],
+                                  ref["cands"], P.to_np(tree["u_accept"]), P.to_np(tree["u_resample"]), True)
+    out = run_tree(tslt, w, tree, ref, renormalised_rule=True)
+    torch.cuda.synchronize()
+    print(P.compare_tree(out, ref, w.expansion, label="config4 renormalised"), "lens", ref["verify"]["len"],
+          "nodes that rejected every candidate:", int(np.count_nonzero(ref["verify"]["node_slot"][:, :n_int] < 0)))
