@@ -1,15 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the TSLT hot path on one MI355X.
 
-One step = one pass of the whole hot path over one batch of synthetic logits already resident in
-HBM: tslt_truncate_sample on every draft row (truncation and the draw of the draft token in one launch),
-tslt_verify (acceptance tests on every target row, then residual / bonus resampling).  Workload:
-BASELINE config "large_vocab" (B=256, gamma=8, V=128256, bf16, T=0.7, top-p 0.9 with K cap 256).  Three
-independent input sets (3.4 GB) are rotated so that the 256 MB Infinity Cache cannot serve repeats.
+One step = one pass of the whole hot path over one batch of synthetic logits already resident in HBM.
+Chain workloads (default: BASELINE config "large_vocab", B=256, gamma=8, V=128256, bf16, T=0.7, top-p 0.9
+with K cap 256): tslt_truncate_sample on every draft row (truncation and the draw of the draft token in
+one launch), tslt_verify_accept on every target row, tslt_verify_resample (residual / bonus token).
+Tree workload ("tree", BASELINE config 4): tslt_truncate on the draft row of every non-leaf node,
+tslt_sample of its candidates, tslt_verify_tree over the whole tree.
+Independent input sets are rotated so that the 256 MB Infinity Cache cannot serve repeats.
 
-Prints ONE JSON line: positions/s (B*gamma per step), the roofline of the dominant kernel measured with an
-event pair per step on the launch stream inside the timed region (an untimed pass with events at every
-boundary gives the per-kernel breakdown first), and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line: positions/s, the roofline of the dominant kernel measured with an event pair per
+step on the launch stream inside the timed region (an untimed pass with events at every boundary gives
+the per-kernel breakdown first), and the CPU oracle timed on a bounded sample.
 """
 import argparse
 import json
@@ -24,48 +26,158 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(w):
-    """Bytes the method has to move per step: every draft and target logit once, the sparse
-    representation once out and once in.  Re-reads (the resampled row) earn no credit."""
-    s = 2 if w.dtype == "bf16" else 4
-    rows_d, rows_t = w.B * w.gamma, w.B * (w.gamma + 1)
-    draft = rows_d * w.V * s
-    sparse_w = rows_d * w.k_cap * (4 + 4 + 4)          # idx, logit, prob written by truncate
-    sparse_r = rows_d * w.k_cap * (4 + 4)              # idx, logit read by verify
-    target = rows_t * w.V * s
-    return {"truncate": draft + sparse_w, "verify_accept": (rows_t - w.B) * w.V * s + sparse_r,
-            "verify_resample": w.B * w.V * s, "total": draft + target + sparse_w + sparse_r}
-
-
-def committed_traffic(kernel):
+def committed_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, or None."""
-    path = os.path.join(ROOT, "profiles", "large_vocab_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
     if not os.path.exists(path):
         return None
     m = re.search(rf"^traffic_bytes_per_launch\s+{kernel}\s+([0-9.eE+]+)", open(path).read(), re.M)
     return float(m.group(1)) if m else None
 
 
-def cpu_baseline(w, host_set, budget_s=20.0):
-    """The oracle as it stands, on the host cores, on a bounded sample of the same workload: whole
-    sequences of one of the timed input sets (copied to the host), as many as fit the time budget."""
-    from oracle import tslt_oracle as O
-    draft, target = host_set["draft"], host_set["target"]
-    t0 = time.perf_counter()
-    done = 0
-    for b in range(w.B):
-        rows = draft[b].float().numpy()
-        tr = O.truncate(rows, w.T, w.top_k, w.top_p, w.k_cap)
-        smp = O.sample(tr["idx"], tr["logit"], tr["count"], host_set["u_sample"][b].numpy().reshape(w.gamma, 1))
-        O.verify_chain_seq(target[b].float().numpy(), w.T, tr["idx"], tr["logit"], tr["count"], smp["token"][:, 0],
-                           host_set["u_accept"][b].numpy(), host_set["u_resample"][b].numpy())
-        done += 1
-        if time.perf_counter() - t0 > budget_s:
-            break
-    dt = time.perf_counter() - t0
-    return {"value": round(done * w.gamma / dt, 2), "unit": "draft positions/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {done} of the {w.B} sequences (x gamma={w.gamma} positions) of input set 0 of the same "
-                      f"workload: truncate+sample+verify, NumPy fp64, one thread, {dt:.1f} s"}
+class ChainPlan:
+    """truncate_sample -> verify_accept -> verify_resample on a chain workload."""
+
+    def __init__(self, w, n_sets, torch, tslt, W, dev):
+        self.w, self.torch, self.tslt = w, torch, tslt
+        B, G, V, K = w.B, w.gamma, w.V, w.k_cap
+        self.sets = [W.make_chain(w, 100 + i, dev) for i in range(n_sets)]
+        i32, f32 = torch.int32, torch.float32
+        # preallocated outputs and workspace: nothing is allocated inside the timed region
+        self.tr = {"idx": torch.empty(B * G, K, dtype=i32, device=dev), "logit": torch.empty(B * G, K, dtype=f32, device=dev),
+                   "prob": torch.empty(B * G, K, dtype=f32, device=dev), "count": torch.empty(B * G, dtype=i32, device=dev),
+                   "mass": torch.empty(B * G, dtype=f32, device=dev), "status": torch.empty(B * G, dtype=i32, device=dev),
+                   "token": torch.empty(B * G, 1, dtype=i32, device=dev), "slot": torch.empty(B * G, 1, dtype=i32, device=dev)}
+        self.vf = {"accept_len": torch.empty(B, dtype=i32, device=dev), "tokens": torch.empty(B, G + 1, dtype=i32, device=dev),
+                   "ratio": torch.empty(B, G, dtype=f32, device=dev), "beta": torch.empty(B, G, dtype=f32, device=dev),
+                   "status": torch.empty(B, dtype=i32, device=dev)}
+        self.ws = torch.empty(tslt.workspace_bytes(tslt.OP_VERIFY, B, G, V, K), dtype=torch.uint8, device=dev)
+        self.positions = B * G
+        s = 2 if w.dtype == "bf16" else 4
+        # bytes the method has to move: every draft and target logit once, the sparse representation once out
+        # and once in; re-reads (the resampled row) earn no credit
+        sparse_w = B * G * K * 12 + B * G * 8
+        sparse_r = B * G * K * 8
+        self.ops = [("truncate", "truncate_kernel", self.truncate, B * G * V * s + sparse_w),
+                    ("verify_accept", "verify_accept_kernel", self.accept, B * G * V * s + sparse_r),
+                    ("verify_resample", "verify_resample_kernel", self.resample, B * V * s)]
+        self.total_bytes = B * G * V * s + B * (G + 1) * V * s + sparse_w + sparse_r
+        self.describe = (f"{w.name}: B={B} gamma={G} V={V} {w.dtype} logits, T={w.T}, top_k={w.top_k}, top_p={w.top_p}, "
+                         f"k_cap={K}; {n_sets} rotating input sets; truncate_sample+verify per step")
+
+    def _verify(self, c, phase):
+        w, t = self.w, self.tr
+        B, G, K = w.B, w.gamma, w.k_cap
+        self.tslt.verify(c["target"], w.T, t["idx"].view(B, G, K), t["logit"].view(B, G, K), t["count"].view(B, G),
+                         t["token"].view(B, G), c["u_accept"], c["u_resample"], out=self.vf, workspace=self.ws, phase=phase)
+
+    def truncate(self, c):
+        w = self.w
+        self.tslt.truncate(c["draft"], w.T, w.top_k, w.top_p, w.k_cap, out=self.tr, u=c["u_sample"].view(w.B * w.gamma, 1))
+
+    def accept(self, c):
+        self._verify(c, "accept")
+
+    def resample(self, c):
+        self._verify(c, "resample")
+
+    def cpu_baseline(self, budget_s=20.0):
+        """The oracle as it stands, on the host cores, on a bounded sample of the same workload: whole
+        sequences of one of the timed input sets (copied to the host), as many as fit the time budget."""
+        from oracle import tslt_oracle as O
+        w = self.w
+        host = {k: v.cpu() for k, v in self.sets[0].items() if self.torch.is_tensor(v)}
+        t0 = time.perf_counter()
+        done = 0
+        for b in range(w.B):
+            tr = O.truncate(host["draft"][b].float().numpy(), w.T, w.top_k, w.top_p, w.k_cap)
+            smp = O.sample(tr["idx"], tr["logit"], tr["count"], host["u_sample"][b].numpy().reshape(w.gamma, 1))
+            O.verify_chain_seq(host["target"][b].float().numpy(), w.T, tr["idx"], tr["logit"], tr["count"], smp["token"][:, 0],
+                               host["u_accept"][b].numpy(), host["u_resample"][b].numpy())
+            done += 1
+            if time.perf_counter() - t0 > budget_s:
+                break
+        dt = time.perf_counter() - t0
+        return {"value": round(done * w.gamma / dt, 2), "unit": "draft positions/s", "cores": 1, "kind": "oracle",
+                "sample": f"first {done} of the {w.B} sequences (x gamma={w.gamma} positions) of input set 0 of the same "
+                          f"workload: truncate+sample+verify, NumPy fp64, one thread, {dt:.1f} s"}
+
+
+class TreePlan:
+    """truncate -> sample (k candidates per non-leaf node) -> verify_tree on the token-tree workload."""
+
+    def __init__(self, w, n_sets, torch, tslt, W, dev):
+        self.w, self.torch, self.tslt = w, torch, tslt
+        self.sets = [W.make_tree(w, 100 + i, dev) for i in range(n_sets)]
+        sh = self.sets[0]["shape"]
+        B, V, K = w.B, w.V, w.k_cap
+        self.n_int, self.n_nodes, self.kmax = sh["n_internal"], sh["n_nodes"], max(w.expansion)
+        n_int, n_nodes, kmax = self.n_int, self.n_nodes, self.kmax
+        i32, f32 = torch.int32, torch.float32
+        R = B * n_int
+        self.tr = {"idx": torch.empty(R, K, dtype=i32, device=dev), "logit": torch.empty(R, K, dtype=f32, device=dev),
+                   "prob": torch.empty(R, K, dtype=f32, device=dev), "count": torch.empty(R, dtype=i32, device=dev),
+                   "mass": torch.empty(R, dtype=f32, device=dev), "status": torch.empty(R, dtype=i32, device=dev)}
+        self.sm = {"token": torch.empty(R, kmax, dtype=i32, device=dev), "slot": torch.empty(R, kmax, dtype=i32, device=dev)}
+        self.vt = {"seq": torch.empty(B, len(w.expansion) + 1, dtype=i32, device=dev), "len": torch.empty(B, dtype=i32, device=dev),
+                   "node_token": None, "node_slot": None, "ratio": torch.empty(B, n_nodes - 1, dtype=f32, device=dev),
+                   "status": torch.empty(B, dtype=i32, device=dev)}
+        self.ws = torch.empty(tslt.workspace_bytes(tslt.OP_VERIFY_TREE_PATH, B, n_nodes, V, K), dtype=torch.uint8, device=dev)
+        if len(set(w.expansion)) != 1:
+            raise SystemExit("bench.py: the tree workload needs the same number of candidates at every layer")
+        self.positions = B * (n_nodes - 1)                 # candidate nodes
+        s = 2 if w.dtype == "bf16" else 4
+        sparse = R * K * 12
+        self.ops = [("truncate", "truncate_kernel", self.truncate, R * V * s + sparse),
+                    ("sample", "sample_kernel", self.sample, R * K * 8),
+                    ("verify_tree", "tree_mcveri_kernel", self.verify, R * V * s + R * K * 8)]
+        self.total_bytes = 2 * R * V * s + sparse + 2 * R * K * 8
+        self.describe = (f"{w.name}: B={B} trees, expansion={tuple(w.expansion)} ({n_int} non-leaf of {n_nodes} nodes), V={V} "
+                         f"{w.dtype} logits, T={w.T}, top_k={w.top_k}, k_cap={K}, candidates drawn "
+                         f"{'without' if w.without_replacement else 'with'} replacement and verified by the matching rule, only "
+                         f"the verified path is sampled; {n_sets} rotating input sets; truncate+sample+verify_tree per step")
+
+    def truncate(self, c):
+        w = self.w
+        self.tslt.truncate(c["draft"], w.T, w.top_k, w.top_p, w.k_cap, out=self.tr)
+
+    def sample(self, c):
+        t = self.tr
+        self.tslt.sample(t["idx"], t["logit"], t["count"], c["u_sample"].view(-1, self.kmax), self.w.without_replacement, out=self.sm)
+
+    def verify(self, c):
+        w, t = self.w, self.tr
+        B, K, n_int = w.B, w.k_cap, self.n_int
+        # children of node n are the kmax consecutive nodes from 1 + n*kmax: the candidates of all non-leaf nodes,
+        # node after node, are the tree's candidate array
+        self.tslt.verify_tree(c["target"], w.T, w.expansion, t["idx"].view(B, n_int, K), t["logit"].view(B, n_int, K),
+                              t["count"].view(B, n_int), self.sm["token"].view(B, n_int * self.kmax), c["u_accept"], c["u_resample"],
+                              all_nodes=False, out=self.vt, workspace=self.ws, without_replacement=w.without_replacement)
+
+    def cpu_baseline(self, budget_s=20.0):
+        """The oracle on whole trees of input set 0, as many as fit the time budget (at least one)."""
+        from oracle import tslt_oracle as O
+        import numpy as np
+        w = self.w
+        c = self.sets[0]
+        n_int, n_nodes, kmax = self.n_int, self.n_nodes, self.kmax
+        t0 = time.perf_counter()
+        done = 0
+        for b in range(w.B):
+            draft = c["draft"][b].float().cpu().numpy()
+            target = c["target"][b].float().cpu().numpy()
+            tr = O.truncate(draft, w.T, w.top_k, w.top_p, w.k_cap)
+            smp = O.sample(tr["idx"], tr["logit"], tr["count"], c["u_sample"][b].cpu().numpy(), w.without_replacement)
+            O.verify_tree_seq(target, w.T, w.expansion, tr["idx"], tr["logit"], tr["count"],
+                              smp["token"].reshape(n_int * kmax).astype(np.int32), c["u_accept"][b].cpu().numpy(),
+                              c["u_resample"][b].cpu().numpy(), w.without_replacement)
+            done += 1
+            if time.perf_counter() - t0 > budget_s:
+                break
+        dt = time.perf_counter() - t0
+        return {"value": round(done * (n_nodes - 1) / dt, 2), "unit": "draft positions/s", "cores": 1, "kind": "oracle",
+                "sample": f"first {done} of the {w.B} trees ({n_nodes - 1} candidate nodes each) of input set 0 of the same "
+                          f"workload, every node evaluated: truncate+sample+verify_tree, NumPy fp64, one thread, {dt:.1f} s"}
 
 
 def main():
@@ -74,7 +186,8 @@ def main():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--workload", default="large_vocab")
-    ap.add_argument("--sets", type=int, default=3, help="independent input sets rotated between steps")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's B (sequences or trees)")
+    ap.add_argument("--sets", type=int, default=0, help="independent input sets rotated between steps (default 3; 1 for tree)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="time the steps without per-kernel events")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
@@ -94,44 +207,22 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     w = W.WORKLOADS[args.workload]
-    B, G, V, K = w.B, w.gamma, w.V, w.k_cap
-
-    sets = []
-    for i in range(args.sets):
-        c = W.make_chain(w, 100 + i, dev)
-        sets.append(c)
-    # preallocated outputs and workspace: nothing is allocated inside the timed region
-    tr_out = {"idx": torch.empty(B * G, K, dtype=torch.int32, device=dev),
-              "logit": torch.empty(B * G, K, dtype=torch.float32, device=dev),
-              "prob": torch.empty(B * G, K, dtype=torch.float32, device=dev),
-              "count": torch.empty(B * G, dtype=torch.int32, device=dev),
-              "mass": torch.empty(B * G, dtype=torch.float32, device=dev),
-              "status": torch.empty(B * G, dtype=torch.int32, device=dev)}
-    tr_out["token"] = torch.empty(B * G, 1, dtype=torch.int32, device=dev)
-    tr_out["slot"] = torch.empty(B * G, 1, dtype=torch.int32, device=dev)
-    vf_out = {"accept_len": torch.empty(B, dtype=torch.int32, device=dev),
-              "tokens": torch.empty(B, G + 1, dtype=torch.int32, device=dev),
-              "ratio": torch.empty(B, G, dtype=torch.float32, device=dev),
-              "beta": torch.empty(B, G, dtype=torch.float32, device=dev),
-              "status": torch.empty(B, dtype=torch.int32, device=dev)}
-    ws = torch.empty(tslt.workspace_bytes(tslt.OP_VERIFY, B, G, V, K), dtype=torch.uint8, device=dev)
-    q_idx, q_logit = tr_out["idx"].view(B, G, K), tr_out["logit"].view(B, G, K)
-    q_count, toks = tr_out["count"].view(B, G), tr_out["token"].view(B, G)
-
-    names = ["truncate", "verify_accept", "verify_resample"]
+    if args.batch > 0:
+        w = W.scaled(w, B=args.batch)
+    is_tree = len(w.expansion) > 0
+    n_sets = args.sets if args.sets > 0 else (1 if is_tree else 3)
+    plan = (TreePlan if is_tree else ChainPlan)(w, n_sets, torch, tslt, W, dev)
+    sets, ops = plan.sets, plan.ops
+    n_ops = len(ops)
 
     def step(c, ev=None):
-        """One pass of the hot path.  ev maps a boundary 0..3 (before truncate ... after resample) to an event."""
+        """One pass of the hot path.  ev maps a boundary 0..n_ops (before the first call ... after the last) to an
+        event."""
         ev = ev or {}
-        if 0 in ev: ev[0].record()
-        tslt.truncate(c["draft"], w.T, w.top_k, w.top_p, K, out=tr_out, u=c["u_sample"].view(B * G, 1))
-        if 1 in ev: ev[1].record()
-        tslt.verify(c["target"], w.T, q_idx, q_logit, q_count, toks, c["u_accept"], c["u_resample"], out=vf_out,
-                    workspace=ws, phase="accept")
-        if 2 in ev: ev[2].record()
-        tslt.verify(c["target"], w.T, q_idx, q_logit, q_count, toks, c["u_accept"], c["u_resample"], out=vf_out,
-                    workspace=ws, phase="resample")
-        if 3 in ev: ev[3].record()
+        for k, (_, _, fn, _) in enumerate(ops):
+            if k in ev: ev[k].record()
+            fn(c)
+        if n_ops in ev: ev[n_ops].record()
 
     def new_events(keys, n):
         return [{k: torch.cuda.Event(enable_timing=True) for k in keys} for _ in range(n)]
@@ -140,28 +231,25 @@ def main():
         step(sets[i % len(sets)])
     torch.cuda.synchronize()
 
-    # untimed pass with an event at every boundary: the per-kernel breakdown, and which kernel dominates
-    alg = algorithmic_bytes(w)
+    # untimed pass with an event at every boundary: the per-kernel breakdown, and which call dominates
     kernels = {}
-    dom = "truncate"
+    dom = 0
     if not args.no_events:
         n_prof = max(3, min(args.steps, 24))
-        pe = new_events(range(4), n_prof)
+        pe = new_events(range(n_ops + 1), n_prof)
         for i in range(n_prof):
             step(sets[i % len(sets)], pe[i])
         torch.cuda.synchronize()
-        for k, name in enumerate(names):
+        for k, (name, _, _, nbytes) in enumerate(ops):
             ts = [pe[i][k].elapsed_time(pe[i][k + 1]) for i in range(n_prof)]
-            kernels[name] = {"avg_ms": round(sum(ts) / len(ts), 4), "min_ms": round(min(ts), 4)}
-        for n in ("truncate", "verify_accept", "verify_resample"):
-            kernels[n]["GBps"] = round(alg[n] / (kernels[n]["avg_ms"] * 1e-3) / 1e9, 1)
-        dom = max(("truncate", "verify_accept"), key=lambda n: kernels[n]["avg_ms"])
+            avg = sum(ts) / len(ts)
+            kernels[name] = {"avg_ms": round(avg, 4), "min_ms": round(min(ts), 4), "GBps": round(nbytes / (avg * 1e-3) / 1e9, 1)}
+        dom = max(range(n_ops), key=lambda k: kernels[ops[k][0]]["avg_ms"])
 
-    # the timed region: K steps; one event pair per step brackets the dominant kernel's launch
+    # the timed region: K steps; one event pair per step brackets the dominant call
     events = None
     if not args.no_events:
-        k0 = names.index(dom)
-        events = new_events((k0, k0 + 1), args.steps)
+        events = new_events((dom, dom + 1), args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -169,30 +257,26 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
-    ms_per_step = dt / args.steps * 1e3
     roofline = None
     if events:
-        k0 = names.index(dom)
-        ts = [events[i][k0].elapsed_time(events[i][k0 + 1]) for i in range(args.steps)]
+        ts = [events[i][dom].elapsed_time(events[i][dom + 1]) for i in range(args.steps)]
         avg_ms = sum(ts) / len(ts)
-        kname = {"truncate": "truncate_kernel", "verify_accept": "verify_accept_kernel"}[dom]
-        achieved = alg[dom] / (avg_ms * 1e-3) / 1e9
+        _, kname, _, nbytes = ops[dom]
+        achieved = nbytes / (avg_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "algorithmic_bytes_per_launch": alg[dom], "avg_launch_ms": round(avg_ms, 4),
-                    "traffic": committed_traffic(kname)}
+                    "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": round(avg_ms, 4),
+                    "traffic": committed_traffic(w.name, kname)}
 
     res = {
         "metric": "draft positions truncated+verified/sec at V=128k; achieved HBM GB/s vs peak",
-        "value": round(B * G * args.steps / dt, 1), "unit": "draft positions/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "value": round(plan.positions * args.steps / dt, 1), "unit": "draft positions/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: B={B} gamma={G} V={V} {w.dtype} logits, T={w.T}, top_p={w.top_p}, "
-                               f"k_cap={K}; {args.sets} rotating input sets; truncate_sample+verify per step",
-                   "storage_dtype": w.dtype},
-        "hbm_GBps_whole_step": round(alg["total"] / (dt / args.steps) / 1e9, 1),
-        "hbm_frac_whole_step": round(alg["total"] / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+        "config": {"workload": plan.describe, "storage_dtype": w.dtype},
+        "hbm_GBps_whole_step": round(plan.total_bytes / (dt / args.steps) / 1e9, 1),
+        "hbm_frac_whole_step": round(plan.total_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
         "kernels_untimed_pass": kernels, "roofline": roofline,
     }
     if args.copy_calibration:
@@ -203,8 +287,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if not args.no_cpu_baseline:
-        host = {k: v.cpu() for k, v in sets[0].items() if torch.is_tensor(v)}
-        res["cpu_baseline"] = cpu_baseline(w, host)
+        res["cpu_baseline"] = plan.cpu_baseline()
     print(json.dumps(res))
 
 
