@@ -128,10 +128,13 @@ class TreePlan:
         self.positions = B * (n_nodes - 1)                 # candidate nodes
         s = 2 if w.dtype == "bf16" else 4
         sparse = R * K * 12
+        # the verified path needs at most depth + 1 target rows per tree (uniforms are indexed by node, so the
+        # nodes off the path never influence the output); every draft row is needed for its candidates
+        path_rows = B * (len(w.expansion) + 1)
         self.ops = [("truncate", "truncate_kernel", self.truncate, R * V * s + sparse),
                     ("sample", "sample_kernel", self.sample, R * K * 8),
-                    ("verify_tree", "tree_mcveri_kernel", self.verify, R * V * s + R * K * 8)]
-        self.total_bytes = 2 * R * V * s + sparse + 2 * R * K * 8
+                    ("verify_tree", "tree_lazy_walk_kernel", self.verify, path_rows * V * s + path_rows * K * 8)]
+        self.total_bytes = R * V * s + sparse + R * K * 8 + path_rows * V * s + path_rows * K * 8
         self.describe = (f"{w.name}: B={B} trees, expansion={tuple(w.expansion)} ({n_int} non-leaf of {n_nodes} nodes), V={V} "
                          f"{w.dtype} logits, T={w.T}, top_k={w.top_k}, k_cap={K}, candidates drawn "
                          f"{'without' if w.without_replacement else 'with'} replacement and verified by the matching rule, only "

@@ -208,14 +208,16 @@ int tslt_verify_resample(const void* target_logits, tslt_dtype dt, int64_t B, in
  *                 accepted candidate and its child number 0..k-1, or, after k rejections, a sample of
  *                 P^(k+1) and -1;
  *                 for a leaf a sample of its target distribution and -1.  Both may be NULL: then only
- *                 the nodes on the verified path are evaluated.
+ *                 the nodes on the verified path are evaluated (depth+1 target rows are read per tree
+ *                 instead of N_nodes; same out_seq, as the uniforms are indexed by node).
  *   out_seq       [B, depth+1] int32 verified sequence: walk from the root, append the node's output,
  *                 descend into the accepted child, stop at the first node without one; -1 after
  *   out_len       [B] int32 length of that sequence, 1..depth+1
- *   out_ratio     [B, N_nodes-1] fp32 p^(i)/q_hat of every candidate that was tested (NaN if an
- *                 earlier sibling was accepted first, -1 if not in the set); may be NULL
- *   status        [B] int32 TSLT_ROW_* bits of the nodes that were evaluated (every non-leaf node, and
- *                 every leaf or only the leaf on the path, see out_node_token); may be NULL
+ *   out_ratio     [B, N_nodes-1] fp32 p^(i)/q^(i) of every candidate that was tested (NaN if an
+ *                 earlier sibling was accepted first or its parent was not evaluated, -1 if not in the
+ *                 set); may be NULL
+ *   status        [B] int32 TSLT_ROW_* bits of the nodes that were evaluated (every node, or only those
+ *                 on the verified path, see out_node_token); may be NULL
  * Workspace: tslt_workspace_bytes(TSLT_OP_VERIFY_TREE, B, N_nodes, V, k_cap) when node outputs are
  * requested, tslt_workspace_bytes(TSLT_OP_VERIFY_TREE_PATH, ...) (much smaller) when both are NULL.
  */

@@ -94,12 +94,13 @@ __device__ __forceinline__ int tree_first_child(const TreeParams& p, int node, i
 // ---------------------------------------------------------------------------------------------
 // Kernel M: Algorithm 5 at one non-leaf node
 // ---------------------------------------------------------------------------------------------
+// Algorithm 5 at non-leaf node `node` of tree b, by all threads of a workgroup.  Writes the node's state,
+// accepted child, number of updates and status to the workspace and the ratios of the candidates it
+// tested; returns the state (0 all candidates rejected, 1 a child accepted, 2 row unusable) and, in
+// `slot`, the accepted child.
 template <typename T>
-__global__ __launch_bounds__(kBlock) void tree_mcveri_kernel(const TreeParams p) {
-  __shared__ VerifyShared sh;
+__device__ __forceinline__ int mcveri_node(const TreeParams& p, int64_t b, int node, VerifyShared& sh, int& slot, int& st) {
   const int tid = threadIdx.x;
-  const int64_t b = blockIdx.x / p.n_int;
-  const int node = int(blockIdx.x - b * p.n_int);
   const int layer = tree_layer(p, node);
   const int k = p.expansion[layer];
   const int c0 = tree_first_child(p, node, layer);           // children are nodes c0 .. c0 + k - 1
@@ -112,7 +113,7 @@ __global__ __launch_bounds__(kBlock) void tree_mcveri_kernel(const TreeParams p)
   int count = p.q_count[r];
   count = count < 0 ? 0 : (count > p.k_cap ? p.k_cap : count);
   double a_s[kSetPer], q_s[kSetPer], p_out;
-  int yi[kSetPer], st;
+  int yi[kSetPer];
   bool ok;
   eval_row_on_set<T>(row, rs, p.V, p.rT, p.k2, p.q_idx + size_t(r) * p.k_cap, p.q_logit + size_t(r) * p.k_cap, count, sh,
                      a_s, q_s, yi, p_out, ok, st);
@@ -169,13 +170,62 @@ __global__ __launch_bounds__(kBlock) void tree_mcveri_kernel(const TreeParams p)
       ++stages;
     }
   }
+  const int state = !ok ? 2 : (accepted >= 0 ? 1 : 0);
   if (tid == 0) {
-    p.node_state[r] = !ok ? 2 : (accepted >= 0 ? 1 : 0);
+    p.node_state[r] = state;
     p.node_slot[r] = accepted;
     p.node_stages[r] = stages;
     p.node_status[r] = st;
   }
+  slot = accepted;
+  return state;
 }
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void tree_mcveri_kernel(const TreeParams p) {
+  __shared__ VerifyShared sh;
+  const int64_t b = blockIdx.x / p.n_int;
+  const int node = int(blockIdx.x - b * p.n_int);
+  int slot, st;
+  mcveri_node<T>(p, b, node, sh, slot, st);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel L (only the verified path is wanted): one workgroup per tree walks from the root, running
+// Algorithm 5 at each node it reaches and descending into the accepted child, so that depth + 1 target rows
+// are read per tree instead of one per non-leaf node.  Uniforms are indexed by node, so the result is the
+// one the all-nodes kernels give.  Leaves the stopping node to kernels S and F.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kBlock) void tree_lazy_walk_kernel(const TreeParams p) {
+  __shared__ VerifyShared sh;
+  const int tid = threadIdx.x;
+  const int64_t b = blockIdx.x;
+  if (p.out_ratio)
+    for (int i = tid; i < p.n_nodes - 1; i += kBlock) p.out_ratio[size_t(b) * (p.n_nodes - 1) + i] = NAN;
+  __syncthreads();
+  int32_t* seq = p.out_seq + size_t(b) * (p.depth + 1);
+  int node = 0, layer = 0, len = 0, st_all = 0;
+  while (node < p.n_int) {
+    int slot, st;
+    const int state = mcveri_node<T>(p, b, node, sh, slot, st);
+    st_all |= st;
+    __syncthreads();
+    if (state != 1) break;
+    const int child = tree_first_child(p, node, layer) + slot;
+    if (tid == 0) seq[len] = p.cand_tokens[size_t(b) * (p.n_nodes - 1) + (child - 1)];
+    ++len;
+    node = child;
+    ++layer;
+  }
+  if (tid == 0) {
+    p.term_node[b] = node;                 // its output is the last token; kernel F writes it
+    p.out_len[b] = len + 1;
+    for (int i = len + 1; i <= p.depth; ++i) seq[i] = -1;
+    p.seq_status[b] = st_all;
+  }
+}
+
 
 // ---------------------------------------------------------------------------------------------
 // Kernel W: the new-sequence search, one wave per tree
@@ -288,9 +338,13 @@ __global__ void tree_status_kernel(const TreeParams p) {
 
 template <typename T> hipError_t launch_verify_tree(TreeParams p, hipStream_t s) {
   hipError_t e;
-  hipLaunchKernelGGL(tree_mcveri_kernel<T>, dim3(unsigned(p.B * p.n_int)), dim3(kBlock), 0, s, p);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(tree_walk_kernel, dim3(unsigned(p.B)), dim3(64), 0, s, p);
+  if (p.all_nodes) {
+    hipLaunchKernelGGL(tree_mcveri_kernel<T>, dim3(unsigned(p.B * p.n_int)), dim3(kBlock), 0, s, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(tree_walk_kernel, dim3(unsigned(p.B)), dim3(64), 0, s, p);
+  } else {
+    hipLaunchKernelGGL(tree_lazy_walk_kernel<T>, dim3(unsigned(p.B)), dim3(kBlock), 0, s, p);
+  }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const int E = ElemTraits<T>::kPerVec;
   int n_seg = int((p.V / E + 1 + kSegVecsTotal - 1) / kSegVecsTotal);
