@@ -2,10 +2,10 @@
 """Benchmark of the TSLT hot path on one MI355X.
 
 One step = one pass of the whole hot path over one batch of synthetic logits already resident in HBM.
-Chain workloads (default: BASELINE config "large_vocab", B=256, gamma=8, V=128256, bf16, T=0.7, top-p 0.9
+Chain workloads (default: benchmark configuration 3, "large_vocab", B=256, gamma=8, V=128256, bf16, T=0.7, top-p 0.9
 with K cap 256): tslt_truncate_sample on every draft row (truncation and the draw of the draft token in
 one launch), tslt_verify_accept on every target row, tslt_verify_resample (residual / bonus token).
-Tree workload ("tree", BASELINE config 4): tslt_truncate on the draft row of every non-leaf node,
+Tree workload ("tree", benchmark configuration 4): tslt_truncate on the draft row of every non-leaf node,
 tslt_sample of its candidates, tslt_verify_tree over the whole tree.
 Independent input sets are rotated so that the 256 MB Infinity Cache cannot serve repeats.
 

@@ -51,7 +51,7 @@ class Workload:
     config_id: int = 0
 
 
-# The five configurations of the benchmark spec (config 2 has two truncation settings).
+# The five benchmark configurations (configuration 2 has two truncation settings).
 WORKLOADS = {
     "tiny": Workload("tiny", B=1, gamma=4, V=32000, dtype="f32", sigma=2.0, boost=(8, 8.0),
                      noise_t=0.5, T=1.0, top_k=16, k_cap=16, config_id=1),

@@ -126,7 +126,7 @@ def test_tree_argument_errors(tslt):
 
 
 def test_tree_config_shape_few_trees(tslt):
-    """BASELINE config 4's shape (depth 5, 4 candidates per node, V=151936, fp32, top-k 32, candidates drawn
+    """Benchmark configuration 4's shape (depth 5, 4 candidates per node, V=151936, fp32, top-k 32, candidates drawn
     without replacement) on 2 trees: 682 draft rows and 2730 target rows, every node evaluated."""
     w = W.scaled(W.WORKLOADS["tree"], B=2)
     tree = W.make_tree(w, 0, DEV)

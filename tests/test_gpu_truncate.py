@@ -160,7 +160,7 @@ def test_tiny_config_end_to_end_truncate(tslt):
 
 
 def test_large_vocab_full_size_sampled_rows(tslt):
-    """BASELINE config 3 at its full size, in the launch configuration bench.py times: every row is
+    """Benchmark configuration 3 at its full size, in the launch configuration bench.py times: every row is
     truncated on the GPU; a sample of rows is checked against the oracle element by element, all rows
     against properties that hold at any size."""
     w = W.WORKLOADS["large_vocab"]

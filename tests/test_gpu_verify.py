@@ -106,7 +106,7 @@ def test_verify_argument_errors(tslt):
 
 
 def test_large_vocab_full_size_sampled_sequences(tslt):
-    """BASELINE config 3 at full size (B=256, gamma=8, V=128256, bf16), the configuration bench.py
+    """Benchmark configuration 3 at full size (B=256, gamma=8, V=128256, bf16), the configuration bench.py
     times: the GPU runs the whole batch; sampled sequences are checked against the oracle, which is fed
     its own truncation of those sequences' draft rows."""
     w = W.WORKLOADS["large_vocab"]
