@@ -88,6 +88,32 @@ def test_unary_tree_equals_chain_verify(tslt):
     print(P.compare_tree(out, ref, w.expansion, label="unary"))
 
 
+@pytest.mark.parametrize("name,kw,rule", [
+    ("widest", dict(B=2, V=2500, expansion=(16,), top_k=24, k_cap=32), False),            # TSLT_MAX_BRANCH candidates
+    ("widest-wor", dict(B=2, V=2500, expansion=(16, 2), top_k=12, k_cap=16), True),       # more candidates than entries
+    ("deepest", dict(B=3, V=600, expansion=(1,) * 16, top_k=0, k_cap=600, without_replacement=False, noise_t=0.02), False),
+])
+def test_tree_limits(tslt, name, kw, rule):
+    """The largest branching factor and depth the library accepts."""
+    w = W.scaled(W.WORKLOADS["tree"], **kw)
+    tree = W.make_tree(w, 13, DEV)
+    ref = oracle_for(w, tree, renormalised_rule=rule)
+    out = run_tree(tslt, w, tree, ref, all_nodes=True, renormalised_rule=rule)
+    path_only = run_tree(tslt, w, tree, ref, all_nodes=False, renormalised_rule=rule)
+    torch.cuda.synchronize()
+    print(name, P.compare_tree(out, ref, w.expansion, all_nodes=True, label=name), "lens", ref["verify"]["len"])
+    if name == "deepest":
+        assert ref["verify"]["len"].max() == 17          # a walk through every layer
+    assert torch.equal(path_only["seq"], out["seq"]) and torch.equal(path_only["len"], out["len"])
+    too_wide = dict(kw, expansion=(17,))
+    with pytest.raises(tslt.TsltError):
+        w2 = W.scaled(W.WORKLOADS["tree"], **too_wide)
+        t2 = W.make_tree(w2, 1, DEV)
+        tslt.verify_tree(t2["target"], w2.T, w2.expansion, t32(ref["q_idx"][:, :1]), t32(ref["q_logit"][:, :1]),
+                         t32(ref["q_count"][:, :1]), torch.zeros(w2.B, 17, dtype=torch.int32, device=DEV),
+                         t2["u_accept"], t2["u_resample"])
+
+
 def test_tree_broken_rows_and_missing_candidates(tslt):
     w = W.scaled(W.WORKLOADS["tree"], B=4, V=4000, expansion=(2, 2), top_k=5, k_cap=8)
     tree = W.make_tree(w, 2, DEV)

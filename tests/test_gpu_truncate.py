@@ -166,8 +166,16 @@ def test_large_vocab_full_size_sampled_rows(tslt):
     w = W.WORKLOADS["large_vocab"]
     c = W.make_chain(w, 0, DEV)
     z = c["draft"].reshape(-1, w.V)
-    out = tslt.truncate(z, w.T, w.top_k, w.top_p, w.k_cap)
+    u = c["u_sample"].reshape(-1, 1)
+    out = tslt.truncate(z, w.T, w.top_k, w.top_p, w.k_cap, u=u)          # tslt_truncate_sample, as bench.py calls it
     torch.cuda.synchronize()
+    plain = tslt.truncate(z, w.T, w.top_k, w.top_p, w.k_cap)
+    for k in plain:
+        assert torch.equal(out[k], plain[k]), k
+    token, slot = out.pop("token"), out.pop("slot")
+    want = O.sample(P.to_np(out["idx"][:96]), P.to_np(out["logit"][:96]), P.to_np(out["count"][:96]), P.to_np(u[:96]), False)
+    assert np.array_equal(P.to_np(token[:96]), want["token"]) and np.array_equal(P.to_np(slot[:96]), want["slot"])
+    assert torch.equal(token[:, 0], torch.gather(out["idx"], 1, slot.long().clamp(min=0))[:, 0])
     rows = np.random.default_rng(0).choice(z.shape[0], 24, replace=False)
     res = P.compare_truncate(out, z[torch.from_numpy(rows).to(DEV)], w.T, w.top_k, w.top_p, w.k_cap, rows=rows,
                              label="large_vocab")
