@@ -216,6 +216,8 @@ int tslt_verify_resample(const void* target_logits, tslt_dtype dt, int64_t B, in
  *   out_ratio     [B, N_nodes-1] fp32 p^(i)/q^(i) of every candidate that was tested (NaN if an
  *                 earlier sibling was accepted first or its parent was not evaluated, -1 if not in the
  *                 set); may be NULL
+ *   out_beta      [B, N_nodes-1] fp32 stage acceptance rate beta^(i) = sum_x min(q^(i)(x), p^(i)(x)) of
+ *                 Section 4.3 for every candidate that was tested (NaN otherwise); may be NULL
  *   status        [B] int32 TSLT_ROW_* bits of the nodes that were evaluated (every node, or only those
  *                 on the verified path, see out_node_token); may be NULL
  * Workspace: tslt_workspace_bytes(TSLT_OP_VERIFY_TREE, B, N_nodes, V, k_cap) when node outputs are
@@ -227,7 +229,7 @@ int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_
                      const int32_t* cand_tokens, const float* u_accept, const float* u_resample,
                      int32_t without_replacement,
                      int32_t* out_node_token, int32_t* out_node_slot, int32_t* out_seq, int32_t* out_len,
-                     float* out_ratio, int32_t* status, void* ws, size_t ws_bytes, void* stream);
+                     float* out_ratio, float* out_beta, int32_t* status, void* ws, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -350,6 +350,7 @@ def mcveri(p, q_idx, q_prob, cands, u_accept, u_resample, without_replacement: b
     amp = np.ones(k)
     gain = 1.0
     betas = []
+    beta = np.full(k, np.nan)               # the same rates, by candidate number
     status = 0
     for i in range(k):
         x = int(cands[i])
@@ -357,6 +358,7 @@ def mcveri(p, q_idx, q_prob, cands, u_accept, u_resample, without_replacement: b
             continue
         amp[i] = gain
         betas.append(float(np.sum(np.minimum(q_i, p_i))))
+        beta[i] = betas[-1]
         if q_i[x] <= 0.0:                   # not in the set (or, without replacement, drawn before)
             status |= STATUS_TOKEN_NOT_IN_SET
             ratio[i] = -1.0
@@ -369,7 +371,7 @@ def mcveri(p, q_idx, q_prob, cands, u_accept, u_resample, without_replacement: b
             margin[i] = abs(ui - bound)
         if accepted:
             return dict(token=x, slot=i, ratio=ratio, accept_margin=margin, cdf_margin=np.inf,
-                        betas=betas, status=status, amp=amp)
+                        betas=betas, beta=beta, status=status, amp=amp)
         r = np.maximum(0.0, p_i - q_i)
         Zr = np.sum(r)
         if Zr > 0.0:                        # always true after a rejection in exact arithmetic
@@ -380,7 +382,7 @@ def mcveri(p, q_idx, q_prob, cands, u_accept, u_resample, without_replacement: b
             rest = np.sum(q_hat)
             q_i = q_hat / rest if rest > 0.0 else q_hat.copy()
     y, mg = inverse_cdf(p_i, u_resample)
-    return dict(token=y, slot=-1, ratio=ratio, accept_margin=margin, cdf_margin=mg, betas=betas,
+    return dict(token=y, slot=-1, ratio=ratio, accept_margin=margin, cdf_margin=mg, betas=betas, beta=beta,
                 status=status, amp=amp)
 
 
@@ -419,6 +421,7 @@ def verify_tree_seq(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, 
     node_token = np.full(n_nodes, -1, np.int32)
     node_slot = np.full(n_nodes, -1, np.int32)
     ratio = np.full(max(n_nodes - 1, 0), np.nan)
+    beta = np.full(max(n_nodes - 1, 0), np.nan)
     acc_margin = np.full(max(n_nodes - 1, 0), np.inf)
     amp = np.ones(max(n_nodes - 1, 0))
     cdf_margin = np.full(n_nodes, np.inf)
@@ -439,6 +442,7 @@ def verify_tree_seq(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, 
                        u_resample[n], without_replacement)
             node_token[n], node_slot[n] = r["token"], r["slot"]
             ratio[c0 - 1:c0 - 1 + k] = r["ratio"]
+            beta[c0 - 1:c0 - 1 + k] = r["beta"]
             acc_margin[c0 - 1:c0 - 1 + k] = r["accept_margin"]
             amp[c0 - 1:c0 - 1 + k] = r["amp"]
             cdf_margin[n] = r["cdf_margin"]
@@ -457,7 +461,7 @@ def verify_tree_seq(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, 
             n = child_node(lay, expansion, n, int(node_slot[n]))
         else:
             break
-    return dict(node_token=node_token, node_slot=node_slot, seq=seq, len=length, path=path, ratio=ratio,
+    return dict(node_token=node_token, node_slot=node_slot, seq=seq, len=length, path=path, ratio=ratio, beta=beta,
                 accept_margin=acc_margin, amp=amp, cdf_margin=cdf_margin, status=status)
 
 
@@ -470,13 +474,13 @@ def verify_tree(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, u_ac
     out = dict(node_token=np.full((B, lay["n_nodes"]), -1, np.int32),
                node_slot=np.full((B, lay["n_nodes"]), -1, np.int32),
                seq=np.full((B, lay["depth"] + 1), -1, np.int32), len=np.zeros(B, np.int32),
-               ratio=np.full((B, lay["n_nodes"] - 1), np.nan),
+               ratio=np.full((B, lay["n_nodes"] - 1), np.nan), beta=np.full((B, lay["n_nodes"] - 1), np.nan),
                accept_margin=np.full((B, lay["n_nodes"] - 1), np.inf), amp=np.ones((B, lay["n_nodes"] - 1)),
                cdf_margin=np.full((B, lay["n_nodes"]), np.inf), status=np.zeros(B, np.int32), path=[])
     for b in range(B):
         r = verify_tree_seq(target[b], T, expansion, q_idx[b], q_logit[b], q_count[b], cand_tokens[b],
                             u_accept[b], u_resample[b], without_replacement)
-        for k in ("node_token", "node_slot", "seq", "ratio", "accept_margin", "amp", "cdf_margin"):
+        for k in ("node_token", "node_slot", "seq", "ratio", "beta", "accept_margin", "amp", "cdf_margin"):
             out[k][b] = r[k]
         out["len"][b] = r["len"]
         out["status"][b] = r["status"]

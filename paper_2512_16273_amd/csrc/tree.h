@@ -40,6 +40,7 @@ struct TreeParams {
   int32_t* out_seq;
   int32_t* out_len;
   float* out_ratio;
+  float* out_beta;        // [B, n_nodes - 1] stage acceptance rate sum_x min(q^(i), p^(i)) of every tested candidate
   int32_t* status;
   // workspace
   int32_t* node_state;    // [B, n_int] 0 all candidates rejected, 1 a child accepted, 2 row unusable
@@ -107,6 +108,7 @@ __device__ __forceinline__ int mcveri_node(const TreeParams& p, int64_t b, int n
   const int32_t* cand = p.cand_tokens + size_t(b) * (p.n_nodes - 1) + (c0 - 1);
   const float* u_acc = p.u_accept + size_t(b) * (p.n_nodes - 1) + (c0 - 1);
   float* ratio_out = p.out_ratio ? p.out_ratio + size_t(b) * (p.n_nodes - 1) + (c0 - 1) : nullptr;
+  float* beta_out = p.out_beta ? p.out_beta + size_t(b) * (p.n_nodes - 1) + (c0 - 1) : nullptr;
   const void* row = tree_row<T>(p, b, node);
   const RowSplit rs = split_row<T>(row, p.V);
   const int64_t r = b * p.n_int + node;
@@ -118,6 +120,7 @@ __device__ __forceinline__ int mcveri_node(const TreeParams& p, int64_t b, int n
   eval_row_on_set<T>(row, rs, p.V, p.rT, p.k2, p.q_idx + size_t(r) * p.k_cap, p.q_logit + size_t(r) * p.k_cap, count, sh,
                      a_s, q_s, yi, p_out, ok, st);
   if (ratio_out && tid < k) ratio_out[tid] = NAN;              // candidates that are never tested
+  if (beta_out && tid < k) beta_out[tid] = NAN;
   int accepted = -1, stages = 0;
   if (ok) {
     double c = 1.0;
@@ -142,6 +145,17 @@ __device__ __forceinline__ int mcveri_node(const TreeParams& p, int64_t b, int n
       __syncthreads();
       if (!found) st |= 4;
       if (ratio_out && tid == 0) ratio_out[i] = float(ratio);
+      if (beta_out) {
+        // Section 4.3's beta^(i): the mass that the stage's proposal and p^(i) share (all of it lies on the set)
+        double shared = 0.0;
+#pragma unroll
+        for (int q = 0; q < kSetPer; ++q) {
+          const double qq = q_s[q] * qscale;
+          shared += (yi[q] >= 0) ? (a_s[q] < qq ? a_s[q] : qq) : 0.0;
+        }
+        shared = block_sum_f64<kWaves>(shared, sh.red);
+        if (tid == 0) beta_out[i] = float(shared);
+      }
       const double bound = ratio < 1.0 ? ratio : 1.0;
       if (found && double(u_acc[i]) < bound) { accepted = i; break; }
       // rejected: p <- norm(max(0, p - q)), q the proposal of this stage
@@ -201,8 +215,10 @@ __global__ __launch_bounds__(kBlock) void tree_lazy_walk_kernel(const TreeParams
   __shared__ VerifyShared sh;
   const int tid = threadIdx.x;
   const int64_t b = blockIdx.x;
-  if (p.out_ratio)
-    for (int i = tid; i < p.n_nodes - 1; i += kBlock) p.out_ratio[size_t(b) * (p.n_nodes - 1) + i] = NAN;
+  for (int i = tid; i < p.n_nodes - 1; i += kBlock) {
+    if (p.out_ratio) p.out_ratio[size_t(b) * (p.n_nodes - 1) + i] = NAN;
+    if (p.out_beta) p.out_beta[size_t(b) * (p.n_nodes - 1) + i] = NAN;
+  }
   __syncthreads();
   int32_t* seq = p.out_seq + size_t(b) * (p.depth + 1);
   int node = 0, layer = 0, len = 0, st_all = 0;

@@ -247,7 +247,7 @@ int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_
                      const float* q_logit, const int32_t* q_count, int32_t k_cap, const int32_t* cand_tokens,
                      const float* u_accept, const float* u_resample, int32_t without_replacement,
                      int32_t* out_node_token, int32_t* out_node_slot, int32_t* out_seq, int32_t* out_len,
-                     float* out_ratio, int32_t* status, void* ws, size_t ws_bytes, void* stream) {
+                     float* out_ratio, float* out_beta, int32_t* status, void* ws, size_t ws_bytes, void* stream) {
   const char* name = "tslt_verify_tree";
   if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "%s: unknown dtype %d", name, int(dt));
   if (B < 0 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "%s: bad shape", name);
@@ -291,7 +291,7 @@ int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_
   p.cand_tokens = cand_tokens; p.u_accept = u_accept; p.u_resample = u_resample;
   p.wor = without_replacement ? 1 : 0;
   p.out_node_token = out_node_token; p.out_node_slot = out_node_slot; p.out_seq = out_seq; p.out_len = out_len;
-  p.out_ratio = out_ratio; p.status = status;
+  p.out_ratio = out_ratio; p.out_beta = out_beta; p.status = status;
   tslt::tree_carve_workspace(p, ws);
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   hipError_t e = dt == TSLT_BF16 ? tslt::launch_verify_tree<tslt::Bf16>(p, s) : tslt::launch_verify_tree<float>(p, s);

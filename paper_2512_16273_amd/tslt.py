@@ -61,7 +61,7 @@ def load(path: Optional[str] = None):
         fn.argtypes = [vp, c.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tslt_verify_tree.restype = c.c_int
     lib.tslt_verify_tree.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, c.POINTER(i32), vp, vp, vp, i32, vp, vp,
-                                     vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+                                     vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -216,7 +216,7 @@ def verify_tree(target: torch.Tensor, temperature: float, expansion: Sequence[in
                 workspace: Optional[torch.Tensor] = None, without_replacement: bool = False) -> dict:
     """tslt_verify_tree: target [B, N_nodes, V]; sparse sets [B, N_int, k_cap]; cand_tokens, u_accept
     [B, N_nodes-1]; u_resample [B, N_nodes].  Returns seq [B, depth+1], len [B], node_token / node_slot
-    [B, N_nodes] (when all_nodes), ratio [B, N_nodes-1], status [B].  without_replacement selects the rule
+    [B, N_nodes] (when all_nodes), ratio and beta [B, N_nodes-1], status [B].  without_replacement selects the rule
     for candidates that were drawn without replacement."""
     lib = load()
     _dev(target, name="target")
@@ -235,6 +235,7 @@ def verify_tree(target: torch.Tensor, temperature: float, expansion: Sequence[in
                "node_token": torch.empty(B, n_nodes, dtype=torch.int32, device=dev) if all_nodes else None,
                "node_slot": torch.empty(B, n_nodes, dtype=torch.int32, device=dev) if all_nodes else None,
                "ratio": torch.empty(B, max(n_nodes - 1, 1), dtype=torch.float32, device=dev),
+               "beta": torch.empty(B, max(n_nodes - 1, 1), dtype=torch.float32, device=dev),
                "status": torch.empty(B, dtype=torch.int32, device=dev)}
     need = workspace_bytes(OP_VERIFY_TREE if all_nodes else OP_VERIFY_TREE_PATH, B, n_nodes, V, k_cap)
     ws = workspace if workspace is not None else _workspace(need, dev)
@@ -244,5 +245,5 @@ def verify_tree(target: torch.Tensor, temperature: float, expansion: Sequence[in
                                 _ptr(u_accept), _ptr(u_resample), 1 if without_replacement else 0,
                                 _ptr(out.get("node_token")),
                                 _ptr(out.get("node_slot")), _ptr(out["seq"]), _ptr(out["len"]), _ptr(out.get("ratio")),
-                                _ptr(out.get("status")), _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
+                                _ptr(out.get("beta")), _ptr(out.get("status")), _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
     return out

@@ -166,4 +166,10 @@ def compare_tree(gpu: dict, ref: dict, expansion, all_nodes=True, label=""):
             err = np.abs(g["ratio"][b][tested] - v["ratio"][b][tested])
             bound = RTOL * np.abs(v["ratio"][b][tested]) + NEAR_TIE * v["amp"][b][tested]
             assert np.all(err <= bound), (tag, float(np.max(err / bound)))
+            if "beta" in g:
+                # stage acceptance rates, to the same scale; NaN exactly where the oracle tested nothing
+                assert np.array_equal(np.isnan(g["beta"][b][tested]), np.isnan(v["beta"][b][tested])), tag
+                err = np.abs(g["beta"][b][tested] - v["beta"][b][tested])
+                bound = RTOL * np.abs(v["beta"][b][tested]) + NEAR_TIE * v["amp"][b][tested]
+                assert np.all(err <= bound), (tag, "beta", float(np.max(err / bound)))
     return dict(trees=B, near_tie_nodes=near_nodes, near_tie_sequences=near_seqs)

@@ -182,6 +182,9 @@ def test_mcveri_reports_stage_betas_and_duplicates_are_rejected():
     p2 = residual_dist(p, qh)
     assert abs(r["betas"][0] - np.minimum(qh, p).sum()) < 1e-14
     assert abs(r["betas"][1] - np.minimum(qh, p2).sum()) < 1e-14
+    # the same rates by candidate number; an absent candidate has none
+    r3 = O.mcveri(p, tr["idx"], qs, [worst, -1, worst], [0.99999994] * 3, 0.25)
+    assert r3["beta"][0] == r["betas"][0] and np.isnan(r3["beta"][1]) and r3["beta"][2] == r["betas"][1]
 
 
 def test_single_candidate_mcveri_is_algorithm_3():
