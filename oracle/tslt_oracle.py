@@ -86,13 +86,32 @@ def _row_status(z32) -> int:
 # ----------------------------------------------------------------------------------------------
 # Section 3.1 / Solution 1: truncate one draft row
 # ----------------------------------------------------------------------------------------------
-def truncate_row(z, T, top_k: int, top_p: float, k_cap: int) -> dict:
+def round_payload(s, payload: str) -> np.ndarray:
+    """The scaled logits as they travel (Section 2.2: b_prob bits per value): "f32" unchanged, "f16" /
+    "bf16" rounded to nearest-even to that 16-bit format and returned as the fp32 values the receiver decodes.
+    Values beyond the format's finite range are clamped to it (a transmitted infinity would be useless)."""
+    s = np.asarray(s, dtype=np.float32)
+    if payload == "f32":
+        return s.copy()
+    if payload == "f16":
+        return np.clip(s, -65504.0, 65504.0).astype(np.float16).astype(np.float32)
+    if payload == "bf16":
+        big = np.float32(3.3895313892515355e38)                  # largest finite bfloat16
+        bits = np.clip(s, -big, big).view(np.uint32).astype(np.uint64)
+        bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000  # round to nearest, ties to even
+        return bits.astype(np.uint32).view(np.float32)
+    raise ValueError(payload)
+
+
+def truncate_row(z, T, top_k: int, top_p: float, k_cap: int, payload: str = "f32") -> dict:
     """Top-K / Top-rho truncation of one row of draft logits and renormalisation.
 
     Returns idx[count], logit[count] (fp32 scaled values, what is transmitted), prob[count]
     (q_hat, fp64), count, mass (rho = sum of q over the kept set; sigma = 1 - mass), margin_rho
     (relative distance of the nucleus test to its decision boundary, inf when the test did not
-    decide the count) and status.
+    decide the count) and status.  With a 16-bit payload the set is chosen as above, the emitted logits
+    are round_payload of the kept ones, and q_hat is the softmax of those rounded values: it is what the
+    receiver reconstructs, so it is what the sender must sample from.
     """
     z32 = np.asarray(z, dtype=np.float32)
     status = _row_status(z32)
@@ -125,11 +144,15 @@ def truncate_row(z, T, top_k: int, top_p: float, k_cap: int) -> dict:
         margin = float(min(cands) / Z)
     head = order[:count]
     Csel = float(np.sum(e[head]))
-    return dict(idx=head.astype(np.int64), logit=s[head].copy(), prob=e[head] / Csel, count=count,
+    if payload == "f32":
+        return dict(idx=head.astype(np.int64), logit=s[head].copy(), prob=e[head] / Csel, count=count,
+                    mass=Csel / Z, margin_rho=margin, status=STATUS_OK)
+    lg = round_payload(s[head], payload)
+    return dict(idx=head.astype(np.int64), logit=lg, prob=sparse_probs(lg, count), count=count,
                 mass=Csel / Z, margin_rho=margin, status=STATUS_OK)
 
 
-def truncate(logits, T, top_k: int, top_p: float, k_cap: int) -> dict:
+def truncate(logits, T, top_k: int, top_p: float, k_cap: int, payload: str = "f32") -> dict:
     """truncate_row over [rows, V]; outputs padded to k_cap (idx -1, logit -inf, prob 0)."""
     logits = np.asarray(logits, dtype=np.float32)
     rows = logits.shape[0]
@@ -138,7 +161,7 @@ def truncate(logits, T, top_k: int, top_p: float, k_cap: int) -> dict:
                mass=np.zeros(rows, np.float64), margin_rho=np.full(rows, np.inf),
                status=np.zeros(rows, np.int32))
     for r in range(rows):
-        t = truncate_row(logits[r], T, top_k, top_p, k_cap)
+        t = truncate_row(logits[r], T, top_k, top_p, k_cap, payload)
         c = t["count"]
         out["idx"][r, :c] = t["idx"]
         out["logit"][r, :c] = t["logit"]
@@ -489,7 +512,7 @@ def verify_tree(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, u_ac
 
 
 # ----------------------------------------------------------------------------------------------
-# Section 2.2: payload model (used only to pin the printed D_V)
+# Section 2.2: payload model, and the wire format of a batch of truncated sets
 # ----------------------------------------------------------------------------------------------
 def index_bits(V: int) -> int:
     """b_idx = ceil(log2 |V|)."""
@@ -499,3 +522,67 @@ def index_bits(V: int) -> int:
 def payload_bits(n_entries: int, b_prob: int, b_idx: int) -> int:
     """D = n * (b_prob + b_idx): n = |V| for a dense distribution, n = K for a truncated one."""
     return int(n_entries) * (int(b_prob) + int(b_idx))
+
+
+def _value_bits16(logit, payload: str) -> np.ndarray:
+    """The 16-bit pattern of every (already rounded) value."""
+    v = round_payload(logit, payload)
+    if payload == "f16":
+        return v.astype(np.float16).view(np.uint16).astype(np.uint64)
+    if payload == "bf16":
+        return (v.view(np.uint32) >> 16).astype(np.uint64)
+    raise ValueError(payload)
+
+
+def pack_rows(idx, logit, count, V: int, payload: str) -> dict:
+    """Wire format of truncated sets (the paper fixes only the size, Section 2.2: K pairs of a b_idx-bit
+    token id and a b_prob-bit value; the layout is this build's).  The stream of one row, least significant
+    bit first: 16 bits count, then per kept entry, in canonical order, b_idx = ceil(log2 V) bits of token id
+    followed by the 16 bits of the value (binary16 or bfloat16).  Rows are padded with zero bits to whole
+    32-bit words and concatenated; row_offset[r] is the first word of row r, row_offset[rows] the total.
+    Bit p of a row's stream is bit p % 32 of its word p // 32.  payload_bits counts only the pairs:
+    sum_r count_r * (b_idx + 16), the D of Section 2.2."""
+    idx = np.asarray(idx)
+    count = np.asarray(count, dtype=np.int64)
+    rows = idx.shape[0]
+    b_idx = index_bits(V)
+    E = b_idx + 16
+    n_words = (16 + count * E + 31) // 32
+    row_offset = np.concatenate([[0], np.cumsum(n_words)]).astype(np.int64)
+    words = np.zeros(int(row_offset[-1]), np.uint32)
+    for r in range(rows):
+        c = int(count[r])
+        stream = int(c)                                     # a Python integer as the bit stream
+        vals = _value_bits16(np.asarray(logit[r][:c], dtype=np.float32), payload)
+        for i in range(c):
+            entry = int(idx[r][i]) | (int(vals[i]) << b_idx)
+            stream |= entry << (16 + i * E)
+        for wd in range(int(n_words[r])):
+            words[row_offset[r] + wd] = (stream >> (32 * wd)) & 0xFFFFFFFF
+    return dict(words=words, row_offset=row_offset, payload_bits=int(np.sum(count)) * E, b_idx=b_idx)
+
+
+def unpack_rows(words, row_offset, rows: int, k_cap: int, V: int, payload: str) -> dict:
+    """Inverse of pack_rows: idx [rows, k_cap] (-1 beyond count), logit (fp32 of the received values, -inf
+    beyond count), count."""
+    words = np.asarray(words, dtype=np.uint32)
+    b_idx = index_bits(V)
+    E = b_idx + 16
+    out = dict(idx=np.full((rows, k_cap), -1, np.int32), logit=np.full((rows, k_cap), -np.inf, np.float32),
+               count=np.zeros(rows, np.int32))
+    for r in range(rows):
+        seg = words[int(row_offset[r]):int(row_offset[r + 1])]
+        stream = 0
+        for wd, x in enumerate(seg):
+            stream |= int(x) << (32 * wd)
+        c = stream & 0xFFFF
+        out["count"][r] = c
+        for i in range(min(c, k_cap)):
+            entry = (stream >> (16 + i * E)) & ((1 << E) - 1)
+            out["idx"][r, i] = entry & ((1 << b_idx) - 1)
+            bits = np.array([entry >> b_idx], dtype=np.uint16)
+            if payload == "f16":
+                out["logit"][r, i] = bits.view(np.float16).astype(np.float32)[0]
+            else:
+                out["logit"][r, i] = (bits.astype(np.uint32) << 16).view(np.float32)[0]
+    return out

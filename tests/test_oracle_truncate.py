@@ -230,3 +230,76 @@ def test_printed_dense_payload():
     assert O.payload_bits(320, 16, O.index_bits(V)) == 9920
     exp = [int(x) for x in vals["expansion"]]
     assert O.tree_layout(exp)["n_internal"] == 1 + 2 + 4
+
+
+# ----------------------------------------------------------------------------------------------
+# 16-bit payloads and the wire format (Section 2.2)
+# ----------------------------------------------------------------------------------------------
+def test_round_payload_is_round_to_nearest_even_of_the_format():
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.normal(0, 8, 4000), [0.0, -0.0, 1.0, 65504.0, 7e4, -7e4, 1e-8, 3e38, 3.4e38]]).astype(np.float32)
+    h = O.round_payload(x, "f16")
+    # nearest: no other binary16 value is closer; brute force over the two neighbours
+    h16 = h.astype(np.float16)
+    assert np.array_equal(h16.astype(np.float32), h)                       # representable
+    with np.errstate(over="ignore"):
+        neighbours = (np.nextafter(h16, np.float16(np.inf)), np.nextafter(h16, np.float16(-np.inf)))
+    for nb in neighbours:
+        ok = np.isfinite(nb.astype(np.float32))
+        xc = np.clip(x, -65504, 65504).astype(np.float64)
+        assert np.all(np.abs(h.astype(np.float64) - xc)[ok] <= np.abs(nb.astype(np.float64) - xc)[ok])
+    assert h[-5] == 65504.0 and h[-4] == -65504.0                         # 7e4 and -7e4: clamped, never infinite
+    b = O.round_payload(x, "bf16")
+    assert np.all((b.view(np.uint32) & 0xFFFF) == 0) and np.all(np.isfinite(b))
+    err = np.abs(b.astype(np.float64) - x.astype(np.float64))
+    ulp = np.ldexp(1.0, np.frexp(np.maximum(np.abs(x.astype(np.float64)), 1e-40))[1] - 8)   # 8 significant bits
+    assert np.all(err[:-2] <= ulp[:-2] * 0.5)
+    tie = np.array([1.00390625], np.float32)                              # 1 + 2^-8: halfway between 1 and 1 + 2^-7
+    assert O.round_payload(tie, "bf16")[0] == 1.0                          # ties to even
+    assert O.round_payload(np.array([1.01171875], np.float32), "bf16")[0] == np.float32(1.015625)
+    assert np.array_equal(O.round_payload(x, "f32"), x)
+
+
+@pytest.mark.parametrize("payload", ["f16", "bf16"])
+def test_truncate_with_a_16_bit_payload(payload):
+    rng = np.random.default_rng(8)
+    z = (rng.normal(0, 3, (6, 900)) - 1.1 * np.log(rng.permutation(900)[None, :] + 1.0)).astype(np.float32)
+    a = O.truncate(z, 0.8, 0, 0.95, 64)
+    b = O.truncate(z, 0.8, 0, 0.95, 64, payload)
+    assert np.array_equal(a["idx"], b["idx"]) and np.array_equal(a["count"], b["count"])   # the set does not move
+    np.testing.assert_allclose(a["mass"], b["mass"], rtol=0, atol=0)
+    for r in range(6):
+        c = b["count"][r]
+        assert np.array_equal(b["logit"][r, :c], O.round_payload(a["logit"][r, :c], payload))
+        # q_hat is the softmax of what is transmitted (scipy's, as an independent routine)
+        from scipy.special import softmax as sp_softmax
+        np.testing.assert_allclose(b["prob"][r, :c], sp_softmax(b["logit"][r, :c].astype(np.float64)), rtol=1e-13)
+        assert abs(b["prob"][r, :c].sum() - 1) < 1e-14
+
+
+@pytest.mark.parametrize("payload,V", [("f16", 32000), ("bf16", 128256), ("f16", 5), ("bf16", 151936)])
+def test_wire_format_round_trip_and_size(payload, V):
+    rng = np.random.default_rng(11)
+    rows, k_cap = 9, 40
+    count = np.array([0, 1, 40, 17, 2, 40, 3, 31, 5])
+    idx = np.full((rows, k_cap), -1, np.int32)
+    logit = np.full((rows, k_cap), -np.inf, np.float32)
+    for r in range(rows):
+        c = count[r]
+        idx[r, :c] = rng.choice(V, c, replace=c > V) if c <= V else rng.integers(0, V, c)
+        logit[r, :c] = O.round_payload(np.sort(rng.normal(0, 5, c))[::-1].astype(np.float32), payload)
+    if count.max() <= V or True:
+        idx[2, 0], idx[2, 1] = V - 1, 0                                    # the extreme token ids
+    pk = O.pack_rows(idx, logit, count, V, payload)
+    b_idx = O.index_bits(V)
+    assert pk["b_idx"] == b_idx and 2 ** b_idx >= V > 2 ** (b_idx - 1) or V <= 2
+    # Section 2.2: D = K (b_prob + b_idx) per position
+    assert pk["payload_bits"] == sum(O.payload_bits(int(c), 16, b_idx) for c in count)
+    assert pk["row_offset"][-1] == len(pk["words"]) == sum((16 + int(c) * (b_idx + 16) + 31) // 32 for c in count)
+    un = O.unpack_rows(pk["words"], pk["row_offset"], rows, k_cap, V, payload)
+    assert np.array_equal(un["count"], count) and np.array_equal(un["idx"], idx)
+    assert np.array_equal(un["logit"], logit)
+    # a hand-built stream: one row, two entries, V = 5 (3 index bits)
+    one = O.pack_rows(np.array([[4, 1]]), np.array([[1.0, -2.0]], np.float32), [2], 5, "bf16")
+    want = 2 | (4 << 16) | (0x3F80 << 19) | (1 << 35) | (0xC000 << 38)
+    assert [int(x) for x in one["words"]] == [want & 0xFFFFFFFF, want >> 32]
