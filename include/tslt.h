@@ -42,7 +42,7 @@
 extern "C" {
 #endif
 
-typedef enum { TSLT_F32 = 0, TSLT_BF16 = 1 } tslt_dtype;
+typedef enum { TSLT_F32 = 0, TSLT_BF16 = 1, TSLT_F16 = 2 /* payload values only */ } tslt_dtype;
 
 enum {
   TSLT_OK = 0,
@@ -93,8 +93,14 @@ size_t tslt_workspace_bytes(int op, int64_t n_outer, int64_t n_inner, int64_t V,
  *               canonical order whose mass, measured against the FULL-vocabulary normaliser, is
  *               >= rho; it is cut at the selection size above without changing that test
  *   k_cap       width of the outputs, 1..TSLT_MAX_K_CAP
+ *   payload     format in which the kept values will travel (Section 2.2's b_prob bits per value):
+ *               TSLT_F32 the scaled logits as computed; TSLT_BF16 / TSLT_F16 each value rounded to nearest-
+ *               even to that format (clamped to its finite range).  The kept set, its count and out_mass do
+ *               not depend on it; out_logit, out_prob and (tslt_truncate_sample) the draws do: q_hat is the
+ *               softmax of the values as the receiver will decode them
  *   out_idx     [rows, k_cap] int32 token ids in canonical order; -1 beyond count
- *   out_logit   [rows, k_cap] fp32 scaled logits s of the kept tokens (the payload); -inf beyond count
+ *   out_logit   [rows, k_cap] fp32 scaled logits s of the kept tokens (the payload; exactly representable
+ *               in the payload format); -inf beyond count
  *   out_prob    [rows, k_cap] fp32 q_hat = q / sum_{kept} q (renormalisation equation); 0 beyond
  *               count; may be NULL
  *   out_count   [rows] int32 size of the kept set
@@ -104,7 +110,7 @@ size_t tslt_workspace_bytes(int op, int64_t n_outer, int64_t n_inner, int64_t V,
  * Workspace: none (ws may be NULL).
  */
 int tslt_truncate(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
-                  float temperature, int32_t top_k, float top_p, int32_t k_cap,
+                  float temperature, int32_t top_k, float top_p, int32_t k_cap, tslt_dtype payload,
                   int32_t* out_idx, float* out_logit, float* out_prob, int32_t* out_count,
                   float* out_mass, int32_t* status, void* ws, size_t ws_bytes, void* stream);
 
@@ -134,11 +140,36 @@ int tslt_sample(const int32_t* idx, const float* logit, const int32_t* count, in
  * Workspace: none.
  */
 int tslt_truncate_sample(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
-                         float temperature, int32_t top_k, float top_p, int32_t k_cap,
+                         float temperature, int32_t top_k, float top_p, int32_t k_cap, tslt_dtype payload,
                          int32_t* out_idx, float* out_logit, float* out_prob, int32_t* out_count,
                          float* out_mass, int32_t* status,
                          const float* u, int32_t n_samples, int32_t* out_token, int32_t* out_slot,
                          void* ws, size_t ws_bytes, void* stream);
+
+/* Wire format of truncated sets (Section 2.2 fixes the size of the payload, K pairs of a b_idx-bit token id
+ * and a b_prob-bit value per position; the layout is defined here).  The stream of one row, least significant
+ * bit first: 16 bits count, then per kept entry, in canonical order, b_idx = ceil(log2 V) bits of token id
+ * followed by the 16 bits of the value (bfloat16 or binary16; values are rounded as by tslt_truncate's
+ * `payload`, so sets truncated with the same format pack without loss).  Rows are padded with zero bits to
+ * whole 32-bit words and concatenated.  Bit p of a row's stream is bit p % 32 of its word p / 32.
+ *
+ *   tslt_pack_bound_words  host function: the words tslt_pack can need for `rows` rows (every row full)
+ *   idx, logit, count      truncated sets as written by tslt_truncate ([rows, k_cap], [rows])
+ *   payload                TSLT_BF16 or TSLT_F16
+ *   out_words              [out_capacity_words] uint32; out_capacity_words >= tslt_pack_bound_words(...)
+ *   out_row_offset         [rows + 1] int64: first word of every row; entry `rows` is the total, so that
+ *                          32 * out_row_offset[rows] bits travel, of which sum_r count_r * (b_idx + 16) are
+ *                          Section 2.2's D
+ * tslt_unpack is the inverse: out_idx / out_logit / out_count as tslt_truncate writes them (-1 / -inf beyond
+ * count).  A count that exceeds k_cap, or what its row's words hold, is cut to that.
+ * Workspace: none.
+ */
+int64_t tslt_pack_bound_words(int64_t rows, int32_t k_cap, int64_t V);
+int tslt_pack(const int32_t* idx, const float* logit, const int32_t* count, int64_t rows, int32_t k_cap, int64_t V,
+              tslt_dtype payload, uint32_t* out_words, int64_t out_capacity_words, int64_t* out_row_offset,
+              void* stream);
+int tslt_unpack(const uint32_t* words, const int64_t* row_offset, int64_t rows, int32_t k_cap, int64_t V,
+                tslt_dtype payload, int32_t* out_idx, float* out_logit, int32_t* out_count, void* stream);
 
 /* Token-sequence verification (Algorithm 3) for B sequences of gamma draft positions.
  *

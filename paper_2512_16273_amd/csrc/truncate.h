@@ -14,6 +14,7 @@
 // evaluated in fp64, which is also where Top-rho and the renormalisation are decided.
 #pragma once
 #include "common.h"
+#include "wire.h"
 #include "exp64.h"
 
 namespace tslt {
@@ -31,6 +32,7 @@ struct TruncateParams {
   float top_p;       // 0 = off
   int k_sel;         // min(top_k (if on), k_cap)
   int k_cap;
+  int payload;       // 0: the scaled logits as computed; 1 / 2: rounded to bfloat16 / binary16 before q_hat and the draws
   int jprime;        // rank (1-based) among the 256 per-thread sample maxima that gives tau0; 0 = always exact path
   int tau_bits;      // number of leading key bits resolved by the threshold search
   int sort_cap;      // capacity of the candidate array
@@ -673,6 +675,29 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
   __syncthreads();
   const double c_sel = count > 0 ? sh.bcast_d[0] : 1.0;
 
+  // what prob and the draws are made of: the kept entries' terms, or, with a 16-bit payload, the terms of
+  // the rounded values (q_hat is the softmax of what the receiver gets)
+  double pw[kMaxPer];
+  double p_excl = excl, p_total = c_sel;
+#pragma unroll
+  for (int r = 0; r < kMaxPer; ++r) pw[r] = e64[r];
+  if (p.payload != kPayloadF32) {
+    const double m_r = double(round_payload(m_s, p.payload));
+    double mine = 0.0;
+#pragma unroll
+    for (int r = 0; r < kMaxPer; ++r) {
+      const int i = tid * per + r;
+      pw[r] = 0.0;
+      if (r < per && i < count) {
+        s32[r] = round_payload(s32[r], p.payload);
+        pw[r] = exp64(double(s32[r]) - m_r);
+        mine += pw[r];
+      }
+    }
+    p_excl = block_excl_scan_f64<NW>(mine, sh.red, p_total);
+    if (!(p_total > 0.0)) p_total = 1.0;
+  }
+
   const size_t out0 = size_t(row_i) * size_t(p.k_cap);
 #pragma unroll
   for (int r = 0; r < kMaxPer; ++r) {
@@ -680,7 +705,7 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
     if (r < per && i < k_eff && i < count) {
       p.out_idx[out0 + i] = int32_t(idx[r]);
       p.out_logit[out0 + i] = s32[r];
-      if (p.out_prob) p.out_prob[out0 + i] = float(e64[r] / c_sel);
+      if (p.out_prob) p.out_prob[out0 + i] = float(pw[r] / p_total);
     }
   }
   for (int i = count + tid; i < p.k_cap; i += NT) {
@@ -697,16 +722,16 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
   if (p.u) {
     for (int c = 0; c < p.n_samples; ++c) {
       const size_t o = size_t(row_i) * p.n_samples + c;
-      const double target = double(p.u[o]) * c_sel;
+      const double target = double(p.u[o]) * p_total;
       int not_above = 0, last_pos = -1;
-      double run = excl;
+      double run = p_excl;
 #pragma unroll
       for (int r = 0; r < kMaxPer; ++r) {
         const int i = tid * per + r;
         if (r < per && i < count) {
-          run += e64[r];
+          run += pw[r];
           not_above += run > target ? 0 : 1;
-          if (e64[r] > 0.0) last_pos = i;
+          if (pw[r] > 0.0) last_pos = i;
         }
       }
       int slot = count > 0 ? block_sum_i32<NW>(not_above, sh.red) : -1;

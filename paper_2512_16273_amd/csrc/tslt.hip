@@ -11,6 +11,7 @@
 #include "common.h"
 #include "sample.h"
 #include "truncate.h"
+#include "wire.h"
 #include "tree.h"
 #include "verify.h"
 
@@ -114,7 +115,7 @@ size_t tslt_workspace_bytes(int op, int64_t n_outer, int64_t n_inner, int64_t V,
 
 // tslt_truncate and tslt_truncate_sample: the second also draws from q_hat in the same launch.
 static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
-                         float temperature, int32_t top_k, float top_p, int32_t k_cap, int32_t* out_idx,
+                         float temperature, int32_t top_k, float top_p, int32_t k_cap, tslt_dtype payload, int32_t* out_idx,
                          float* out_logit, float* out_prob, int32_t* out_count, float* out_mass, int32_t* status,
                          const float* u, int32_t n_samples, int32_t* out_token, int32_t* out_slot,
                          void* ws, size_t ws_bytes, void* stream) {
@@ -124,6 +125,7 @@ static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_
   if (!(temperature > 0.0f) || !std::isfinite(temperature)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: temperature must be > 0");
   if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "tslt_truncate: k_cap must be in 1..%d", TSLT_MAX_K_CAP);
   if (top_k < 0 || !(top_p >= 0.0f)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: top_k and top_p must be >= 0");
+  if (payload != TSLT_F32 && payload != TSLT_BF16 && payload != TSLT_F16) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: unknown payload format %d", int(payload));
   if (rows == 0) return TSLT_OK;
   if (!logits || !out_idx || !out_logit || !out_count) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: null pointer");
   if (reinterpret_cast<uintptr_t>(logits) % (dt == TSLT_BF16 ? 2 : 4)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: logits not aligned to their element type");
@@ -134,6 +136,7 @@ static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_
   p.k2 = log2e_over_T(p.rT);
   p.top_p = (top_p > 0.0f && top_p < 1.0f) ? top_p : 0.0f;
   p.k_cap = k_cap;
+  p.payload = int(payload);
   p.k_sel = (top_k > 0 && top_k < k_cap) ? top_k : k_cap;
   p.out_idx = out_idx; p.out_logit = out_logit; p.out_prob = out_prob; p.out_count = out_count;
   p.out_mass = out_mass; p.status = status;
@@ -158,23 +161,69 @@ static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_
 }
 
 int tslt_truncate(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
-                  float temperature, int32_t top_k, float top_p, int32_t k_cap, int32_t* out_idx,
+                  float temperature, int32_t top_k, float top_p, int32_t k_cap, tslt_dtype payload, int32_t* out_idx,
                   float* out_logit, float* out_prob, int32_t* out_count, float* out_mass, int32_t* status,
                   void* ws, size_t ws_bytes, void* stream) {
-  return truncate_impl(logits, dt, rows, V, row_stride, temperature, top_k, top_p, k_cap, out_idx, out_logit, out_prob,
+  return truncate_impl(logits, dt, rows, V, row_stride, temperature, top_k, top_p, k_cap, payload, out_idx, out_logit, out_prob,
                        out_count, out_mass, status, nullptr, 0, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 int tslt_truncate_sample(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
-                         float temperature, int32_t top_k, float top_p, int32_t k_cap, int32_t* out_idx,
+                         float temperature, int32_t top_k, float top_p, int32_t k_cap, tslt_dtype payload, int32_t* out_idx,
                          float* out_logit, float* out_prob, int32_t* out_count, float* out_mass, int32_t* status,
                          const float* u, int32_t n_samples, int32_t* out_token, int32_t* out_slot,
                          void* ws, size_t ws_bytes, void* stream) {
   if (n_samples < 1 || n_samples > TSLT_MAX_BRANCH)
     return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate_sample: n_samples must be in 1..%d", TSLT_MAX_BRANCH);
   if (rows > 0 && (!u || !out_token)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate_sample: null pointer");
-  return truncate_impl(logits, dt, rows, V, row_stride, temperature, top_k, top_p, k_cap, out_idx, out_logit, out_prob,
+  return truncate_impl(logits, dt, rows, V, row_stride, temperature, top_k, top_p, k_cap, payload, out_idx, out_logit, out_prob,
                        out_count, out_mass, status, u, n_samples, out_token, out_slot, ws, ws_bytes, stream);
+}
+
+int64_t tslt_pack_bound_words(int64_t rows, int32_t k_cap, int64_t V) {
+  if (rows <= 0 || k_cap < 1 || k_cap > TSLT_MAX_K_CAP || V < 1 || V > 0x7FFFFFFF) return 0;
+  return rows * tslt::wire_row_words(k_cap, tslt::wire_index_bits(V));
+}
+
+int tslt_pack(const int32_t* idx, const float* logit, const int32_t* count, int64_t rows, int32_t k_cap, int64_t V,
+              tslt_dtype payload, uint32_t* out_words, int64_t out_capacity_words, int64_t* out_row_offset,
+              void* stream) {
+  if (rows < 0 || V < 1 || V > 0x7FFFFFFF) return fail(TSLT_ERR_INVALID_ARG, "tslt_pack: bad shape");
+  if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "tslt_pack: k_cap must be in 1..%d", TSLT_MAX_K_CAP);
+  if (payload != TSLT_BF16 && payload != TSLT_F16) return fail(TSLT_ERR_INVALID_ARG, "tslt_pack: the value format must be bfloat16 or binary16");
+  if (!out_row_offset) return fail(TSLT_ERR_INVALID_ARG, "tslt_pack: null pointer");
+  if (rows > 0 && (!idx || !logit || !count || !out_words)) return fail(TSLT_ERR_INVALID_ARG, "tslt_pack: null pointer");
+  if (out_capacity_words < tslt_pack_bound_words(rows, k_cap, V))
+    return fail(TSLT_ERR_WORKSPACE, "tslt_pack: room for %lld words, %lld may be needed", (long long)out_capacity_words,
+                (long long)tslt_pack_bound_words(rows, k_cap, V));
+  tslt::WireParams p{};
+  p.idx = idx; p.logit = logit; p.count = count; p.rows = rows; p.k_cap = k_cap; p.b_idx = tslt::wire_index_bits(V);
+  p.payload = int(payload); p.words = out_words; p.row_offset = out_row_offset;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  hipError_t e;
+  hipLaunchKernelGGL(tslt::wire_offsets_kernel, dim3(1), dim3(1024), 0, s, p);
+  if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "tslt_pack launch");
+  if (rows > 0) {
+    hipLaunchKernelGGL(tslt::wire_pack_kernel, dim3(unsigned(rows)), dim3(64), 0, s, p);
+    if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "tslt_pack launch");
+  }
+  return TSLT_OK;
+}
+
+int tslt_unpack(const uint32_t* words, const int64_t* row_offset, int64_t rows, int32_t k_cap, int64_t V,
+                tslt_dtype payload, int32_t* out_idx, float* out_logit, int32_t* out_count, void* stream) {
+  if (rows < 0 || V < 1 || V > 0x7FFFFFFF) return fail(TSLT_ERR_INVALID_ARG, "tslt_unpack: bad shape");
+  if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "tslt_unpack: k_cap must be in 1..%d", TSLT_MAX_K_CAP);
+  if (payload != TSLT_BF16 && payload != TSLT_F16) return fail(TSLT_ERR_INVALID_ARG, "tslt_unpack: the value format must be bfloat16 or binary16");
+  if (rows == 0) return TSLT_OK;
+  if (!words || !row_offset || !out_idx || !out_logit || !out_count) return fail(TSLT_ERR_INVALID_ARG, "tslt_unpack: null pointer");
+  tslt::WireParams p{};
+  p.in_words = words; p.in_row_offset = row_offset; p.rows = rows; p.k_cap = k_cap; p.b_idx = tslt::wire_index_bits(V);
+  p.payload = int(payload); p.out_idx = out_idx; p.out_logit = out_logit; p.out_count = out_count;
+  hipLaunchKernelGGL(tslt::wire_unpack_kernel, dim3(unsigned(rows)), dim3(64), 0, reinterpret_cast<hipStream_t>(stream), p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e, "tslt_unpack launch");
+  return TSLT_OK;
 }
 
 int tslt_sample(const int32_t* idx, const float* logit, const int32_t* count, int64_t rows, int32_t k_cap,

@@ -20,8 +20,10 @@ F32, BF16 = 0, 1
 OP_TRUNCATE, OP_SAMPLE, OP_VERIFY, OP_VERIFY_TREE, OP_VERIFY_TREE_PATH = 0, 1, 2, 3, 4
 ROW_NONFINITE, ROW_EMPTY, ROW_TOKEN_NOT_IN_SET, ROW_EXACT_PATH = 1, 2, 4, 256
 MAX_K_CAP = 1024
+PAYLOAD = {"f32": 0, "bf16": 1, "f16": 2}       # tslt_dtype codes of the formats a payload can travel in
 
 EXPORTS = ("tslt_version", "tslt_last_error", "tslt_workspace_bytes", "tslt_truncate", "tslt_truncate_sample", "tslt_sample",
+           "tslt_pack_bound_words", "tslt_pack", "tslt_unpack",
            "tslt_verify", "tslt_verify_accept", "tslt_verify_resample", "tslt_verify_tree")
 
 _lib = None
@@ -50,9 +52,15 @@ def load(path: Optional[str] = None):
     lib.tslt_workspace_bytes.restype = sz
     lib.tslt_workspace_bytes.argtypes = [c.c_int, i64, i64, i64, i32]
     lib.tslt_truncate.restype = c.c_int
-    lib.tslt_truncate.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tslt_truncate.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, f32, i32, c.c_int, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tslt_pack_bound_words.restype = i64
+    lib.tslt_pack_bound_words.argtypes = [i64, i32, i64]
+    lib.tslt_pack.restype = c.c_int
+    lib.tslt_pack.argtypes = [vp, vp, vp, i64, i32, i64, c.c_int, vp, i64, vp, vp]
+    lib.tslt_unpack.restype = c.c_int
+    lib.tslt_unpack.argtypes = [vp, vp, i64, i32, i64, c.c_int, vp, vp, vp, vp]
     lib.tslt_truncate_sample.restype = c.c_int
-    lib.tslt_truncate_sample.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, f32, i32, vp, vp, vp, vp, vp, vp,
+    lib.tslt_truncate_sample.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, f32, i32, c.c_int, vp, vp, vp, vp, vp, vp,
                                          vp, i32, vp, vp, vp, sz, vp]
     lib.tslt_sample.restype = c.c_int
     lib.tslt_sample.argtypes = [vp, vp, vp, i64, i32, vp, i32, i32, vp, vp, vp]
@@ -121,10 +129,12 @@ def _workspace(nbytes: int, device) -> Optional[torch.Tensor]:
 
 
 def truncate(logits: torch.Tensor, temperature: float, top_k: int, top_p: float, k_cap: int,
-             want_prob: bool = True, out: Optional[dict] = None, u: Optional[torch.Tensor] = None) -> dict:
+             want_prob: bool = True, out: Optional[dict] = None, u: Optional[torch.Tensor] = None,
+             payload: str = "f32") -> dict:
     """tslt_truncate over logits [..., V].  Returns idx, logit, prob, count, mass, status ([rows, k_cap] /
     [rows]).  With uniforms u [rows, n] it is tslt_truncate_sample: the result also holds token, slot
-    [rows, n], n i.i.d. draws from each row's q_hat."""
+    [rows, n], n i.i.d. draws from each row's q_hat.  payload = "bf16" / "f16" rounds the kept values to the
+    format in which they will travel before q_hat and the draws are computed."""
     lib = load()
     _dev(logits, name="logits", contiguous=False)
     rows, V, stride = _rows_2d(logits)
@@ -140,7 +150,7 @@ def truncate(logits: torch.Tensor, temperature: float, top_k: int, top_p: float,
         }
     if u is None:
         _check(lib.tslt_truncate(_ptr(logits), _dtype_code(logits), rows, V, stride, float(temperature), int(top_k),
-                                 float(top_p), int(k_cap), _ptr(out["idx"]), _ptr(out["logit"]), _ptr(out.get("prob")),
+                                 float(top_p), int(k_cap), PAYLOAD[payload], _ptr(out["idx"]), _ptr(out["logit"]), _ptr(out.get("prob")),
                                  _ptr(out["count"]), _ptr(out.get("mass")), _ptr(out.get("status")), None, 0, _stream()))
         return out
     _dev(u, torch.float32, "u")
@@ -150,10 +160,36 @@ def truncate(logits: torch.Tensor, temperature: float, top_k: int, top_p: float,
         out["token"] = torch.empty(rows, n, dtype=torch.int32, device=dev)
         out["slot"] = torch.empty(rows, n, dtype=torch.int32, device=dev)
     _check(lib.tslt_truncate_sample(_ptr(logits), _dtype_code(logits), rows, V, stride, float(temperature), int(top_k),
-                                    float(top_p), int(k_cap), _ptr(out["idx"]), _ptr(out["logit"]),
+                                    float(top_p), int(k_cap), PAYLOAD[payload], _ptr(out["idx"]), _ptr(out["logit"]),
                                     _ptr(out.get("prob")), _ptr(out["count"]), _ptr(out.get("mass")),
                                     _ptr(out.get("status")), _ptr(u2), n, _ptr(out["token"]), _ptr(out.get("slot")),
                                     None, 0, _stream()))
+    return out
+
+
+def pack(idx: torch.Tensor, logit: torch.Tensor, count: torch.Tensor, V: int, payload: str) -> dict:
+    """tslt_pack: truncated sets [rows, k_cap] -> words (uint32, as int32 storage), row_offset [rows + 1] int64."""
+    lib = load()
+    _dev(idx, torch.int32, "idx"); _dev(logit, torch.float32, "logit"); _dev(count, torch.int32, "count")
+    rows, k_cap = idx.shape
+    cap = int(lib.tslt_pack_bound_words(rows, k_cap, V))
+    words = torch.zeros(max(cap, 1), dtype=torch.int32, device=idx.device)
+    offs = torch.empty(rows + 1, dtype=torch.int64, device=idx.device)
+    _check(lib.tslt_pack(_ptr(idx), _ptr(logit), _ptr(count), rows, k_cap, int(V), PAYLOAD[payload], _ptr(words), cap,
+                         _ptr(offs), _stream()))
+    return {"words": words, "row_offset": offs}
+
+
+def unpack(words: torch.Tensor, row_offset: torch.Tensor, rows: int, k_cap: int, V: int, payload: str) -> dict:
+    """tslt_unpack: the inverse of pack -> idx, logit [rows, k_cap], count [rows]."""
+    lib = load()
+    _dev(words, torch.int32, "words"); _dev(row_offset, torch.int64, "row_offset")
+    dev = words.device
+    out = {"idx": torch.empty(rows, k_cap, dtype=torch.int32, device=dev),
+           "logit": torch.empty(rows, k_cap, dtype=torch.float32, device=dev),
+           "count": torch.empty(rows, dtype=torch.int32, device=dev)}
+    _check(lib.tslt_unpack(_ptr(words), _ptr(row_offset), rows, k_cap, int(V), PAYLOAD[payload], _ptr(out["idx"]),
+                           _ptr(out["logit"]), _ptr(out["count"]), _stream()))
     return out
 
 

@@ -52,10 +52,12 @@ def test_argument_errors_are_found_on_the_host(lib):
     lib.tslt_last_error.restype = ctypes.c_char_p
     vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
     lib.tslt_truncate.restype = ctypes.c_int
-    lib.tslt_truncate.argtypes = [vp, ctypes.c_int, i64, i64, i64, f32, i32, f32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tslt_truncate.argtypes = [vp, ctypes.c_int, i64, i64, i64, f32, i32, f32, i32, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp,
+                                  sz, vp]
     fake = ctypes.c_void_p(0x1000)
-    def call(dt=1, rows=4, V=1000, stride=1000, T=1.0, k=4, p=0.0, cap=4, ptr=fake):
-        return lib.tslt_truncate(ptr, dt, rows, V, stride, T, k, p, cap, fake, fake, None, fake, None, None, None, 0, None)
+    def call(dt=1, rows=4, V=1000, stride=1000, T=1.0, k=4, p=0.0, cap=4, ptr=fake, payload=0):
+        return lib.tslt_truncate(ptr, dt, rows, V, stride, T, k, p, cap, payload, fake, fake, None, fake, None, None, None,
+                                 0, None)
     assert call(T=0.0) == -1 and b"temperature" in lib.tslt_last_error()
     assert call(dt=7) == -1
     assert call(stride=10) == -1
@@ -64,6 +66,20 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert call(ptr=None) == -1
     assert call(ptr=ctypes.c_void_p(0x1001)) == -1                          # bf16 row at an odd address
     assert call(rows=0) == 0                                                 # empty batch: nothing to do
+    assert call(payload=5) == -1 and b"payload" in lib.tslt_last_error()
+    # wire format: sizes and argument checks
+    lib.tslt_pack_bound_words.restype = i64
+    lib.tslt_pack_bound_words.argtypes = [i64, i32, i64]
+    assert lib.tslt_pack_bound_words(3, 256, 128256) == 3 * ((16 + 256 * (17 + 16) + 31) // 32)
+    assert lib.tslt_pack_bound_words(1, 1, 1) == 1 and lib.tslt_pack_bound_words(1, 1024, 2 ** 31 - 1) == (16 + 1024 * 47 + 31) // 32
+    lib.tslt_pack.restype = ctypes.c_int
+    lib.tslt_pack.argtypes = [vp, vp, vp, i64, i32, i64, ctypes.c_int, vp, i64, vp, vp]
+    assert lib.tslt_pack(fake, fake, fake, 4, 16, 1000, 0, fake, 10 ** 6, fake, None) == -1      # fp32 is not a wire format
+    assert lib.tslt_pack(fake, fake, fake, 4, 16, 1000, 1, fake, 3, fake, None) == -3            # too little room
+    lib.tslt_unpack.restype = ctypes.c_int
+    lib.tslt_unpack.argtypes = [vp, vp, i64, i32, i64, ctypes.c_int, vp, vp, vp, vp]
+    assert lib.tslt_unpack(fake, fake, 4, 4096, 1000, 2, fake, fake, fake, None) == -2
+    assert lib.tslt_unpack(None, fake, 4, 16, 1000, 2, fake, fake, fake, None) == -1
     lib.tslt_sample.restype = ctypes.c_int
     lib.tslt_sample.argtypes = [vp, vp, vp, i64, i32, vp, i32, i32, vp, vp, vp]
     assert lib.tslt_sample(fake, fake, fake, 4, 2048, fake, 1, 0, fake, None, None) == -2
