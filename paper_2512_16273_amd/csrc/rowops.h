@@ -375,7 +375,6 @@ __device__ __forceinline__ void sweep_segment_direct(const RowSplit& rs, int seg
 template <typename T>
 __device__ __forceinline__ void sweep_group(const void* row, const RowSplit& rs, int group, bool check, float rT,
                                             const double* table, SegResult* segs, double* subs, VerifyShared& sh) {
-  constexpr int E = ElemTraits<T>::kPerVec;
   const int tid = threadIdx.x;
   const int n_seg_row = int((rs.nvec + kSegVecsTotal - 1) / kSegVecsTotal);
   const int seg0 = group * kGroupSegs;

@@ -41,12 +41,6 @@ float log2e_over_T(float rT) { return float(double(rT) * 1.4426950408889634074);
 
 constexpr size_t kMaxLds = 160 * 1024;   // LDS of one gfx950 compute unit
 
-int next_pow2(int v) {
-  int p = 1;
-  while (p < v) p <<= 1;
-  return p;
-}
-
 // Launch plan of the truncate kernel: which rank among the per-thread sample maxima gives the
 // threshold, and how large the candidate array has to be.  Returns the bytes of dynamic LDS.
 size_t plan_truncate(tslt_dtype dt, int64_t V, int nt, tslt::TruncateParams& p) {
