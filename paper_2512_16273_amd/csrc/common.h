@@ -254,9 +254,10 @@ template <int NW> __device__ __forceinline__ int block_excl_scan_i32(int v, Bloc
 // same array; `tmp` must be distinct from both.  hist, start and cursor are 256-entry LDS arrays.
 // Work per thread is about n/256 + k_keep/256 * mean bin population; values crowded into one bin cost
 // more, bounded by n^2/256 comparisons per thread.  NT = threads of the workgroup (64, 128 or 256).
-__device__ __forceinline__ int value_bin(uint64_t c, double vmin, double scale) {
-  const int b = int((double(cand_value(c)) - vmin) * scale);
-  return b > 255 ? 255 : b;
+__device__ __forceinline__ int value_bin(uint64_t c, float vmin, float scale) {
+  // fp32 subtraction and multiplication are monotone, which is all the binning has to be
+  const int b = int((cand_value(c) - vmin) * scale);
+  return b > 255 ? 255 : (b < 0 ? 0 : b);
 }
 template <int NT>
 __device__ __forceinline__ bool bucket_sort_desc(const uint64_t* in, int n, uint64_t* tmp, int tmp_cap, uint64_t* out,
@@ -283,9 +284,9 @@ __device__ __forceinline__ bool bucket_sort_desc(const uint64_t* in, int n, uint
     kmin = uint32_t(red.i[w]) < kmin ? uint32_t(red.i[w]) : kmin;
     kmax = uint32_t(red.i[8 + w]) > kmax ? uint32_t(red.i[8 + w]) : kmax;
   }
-  const double vmin = double(key_to_f32(kmin));
-  const double span = double(key_to_f32(kmax)) - vmin;
-  const double scale = (span > 0.0 && span < 1e300) ? 255.0 / span : 0.0;
+  const float vmin = key_to_f32(kmin);
+  const float span = key_to_f32(kmax) - vmin;            // may overflow to +inf: then one bin
+  const float scale = (span > 0.0f && span < 3.0e38f) ? 255.0f / span : 0.0f;
   for (int i = tid; i < n; i += NT) atomicAdd(&hist[value_bin(in[i], vmin, scale)], 1u);
   __syncthreads();
   int total;

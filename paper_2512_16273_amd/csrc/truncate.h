@@ -22,7 +22,7 @@ namespace tslt {
 constexpr int kTruncThreads = 256;   // threads of a truncate workgroup (one row each)
 constexpr int kBatch = 4;        // tiles per batch; the first batch is the threshold sample
 constexpr int kDepth = 2;        // batches in flight per thread during the pass
-constexpr int kRing = 48;      // pairs of vectors a wave can park; expanded when a third full
+constexpr int kRing = 96;      // vectors a wave can park; expanded when a third full
 
 struct TruncateParams {
   const void* logits;
@@ -54,8 +54,7 @@ struct TruncateParams {
 
 // Dynamic LDS: [ rings ] [ candidates, then sort scratch ].  The ring space is
 // reused for the sort's three 256-entry tables and, before the pass, for the per-thread sample maxima.
-constexpr int kHitList = 192;   // positions a wave can collect in one expansion (a ring holds kRing * 16 elements)
-constexpr int ring_bytes_for(int n_waves) { return n_waves * (kRing * 40 + kHitList * 2); }
+constexpr int ring_bytes_for(int n_waves) { return n_waves * (kRing * 20); }      // per slot a vector and its index
 static_assert(ring_bytes_for(2) >= 3 * 256 * 4, "ring space must hold the sort tables");
 inline size_t truncate_lds_bytes(int ring_bytes, int lds_recs) { return size_t(ring_bytes) + size_t(8) * lds_recs; }
 inline int truncate_sort_scratch(int k_sel) { return k_sel + k_sel / 2 + 64; }   // records the sort may need
@@ -294,56 +293,54 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
   return n <= cap ? n : -1;
 }
 
-// A ring slot holds a pair of 16-byte vectors of which at least one element is above tau0, and the
-// index (in vectors, within the row's aligned body) of each.
-struct RingPair { uint4 w[2]; };
-
-// Expands the hit pairs parked in a wave's ring into candidate records (elements above tau0).  The
-// n pairs are n * 2E consecutive elements in LDS.  Stage 1 sweeps them 64 at a time, one element per
-// lane, and packs the positions of the elements above tau0 into a per-wave list; stage 2 turns that
-// dense list into records, one per lane, after a single reservation in the shared candidate array.
-template <typename T> __device__ __forceinline__ float ring_elem(const unsigned char* ring, uint32_t g);
-template <> __device__ __forceinline__ float ring_elem<float>(const unsigned char* ring, uint32_t g) {
-  return reinterpret_cast<const float*>(ring)[g];
-}
-template <> __device__ __forceinline__ float ring_elem<Bf16>(const unsigned char* ring, uint32_t g) {
-  return as_f32(uint32_t(reinterpret_cast<const uint16_t*>(ring)[g]) << 16);
-}
-
+// A ring slot holds a 16-byte vector of which at least one element is above tau0, and its index (in
+// vectors, within the row's aligned body).
+//
+// Expands the n vectors parked in a wave's ring into candidate records (elements above tau0).  Lane s
+// takes slot s: it marks which of the vector's elements are above tau0, a wave scan of the counts gives
+// every lane its place behind a single reservation in the shared candidate array, and the marked elements
+// are written there.
 template <typename T>
-__device__ __forceinline__ void expand_ring(const RingPair* ring, const uint2* ring_vidx, uint16_t* hitlist, int n,
-                                            float tau0, uint32_t head, uint64_t* cand, int cap, TruncateShared& sh,
-                                            int& lost) {
+__device__ __forceinline__ void expand_ring(const uint4* ring, const uint32_t* ring_vidx, int n, float tau0,
+                                            uint32_t head, uint64_t* cand, int cap, TruncateShared& sh, int& lost) {
   constexpr int E = ElemTraits<T>::kPerVec;
-  const unsigned char* bytes = reinterpret_cast<const unsigned char*>(ring);
-  const uint32_t lane = uint32_t(lane_id());
-  const uint32_t total = uint32_t(n) * 2 * E;
-  int hcnt = 0;
-  for (uint32_t g0 = 0; g0 < total; g0 += 64) {
-    const uint32_t g = g0 + lane;
-    const bool hit = g < total && ring_elem<T>(bytes, g) > tau0;
-    const uint64_t mask = ballot(hit);
-    if (mask != 0) {
-      const int pos = hcnt + lanes_below(mask);
-      if (hit && pos < kHitList) hitlist[pos] = uint16_t(g);
-      hcnt += __popcll(mask);
+  const int lane = lane_id();
+  for (int s0 = 0; s0 < n; s0 += 64) {
+    const int s = s0 + lane;
+    float v[E];
+    uint32_t vi = 0;
+    int cnt = 0;
+    if (s < n) {
+      unpack<T>(ring[s], v);
+      vi = ring_vidx[s];
+#pragma unroll
+      for (int e = 0; e < E; ++e) cnt += v[e] > tau0 ? 1 : 0;
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e) v[e] = -INFINITY;
+    }
+    int incl = cnt;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    const int total = __shfl(incl, 63, 64);
+    if (total == 0) continue;
+    int base = 0;
+    if (lane == 0) base = atomicAdd(&sh.cand_count, total);
+    base = __builtin_amdgcn_readfirstlane(base);
+    int pos = base + incl - cnt;
+    const uint32_t idx0 = head + vi * E;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      if (v[e] > tau0) {
+        if (pos < cap) cand[pos] = make_cand(v[e], idx0 + e);
+        ++pos;
+      }
     }
   }
-  if (hcnt > kHitList) { lost = 1; hcnt = kHitList; }
-  if (hcnt == 0) return;
-  int base = 0;
-  if (lane == 0) base = atomicAdd(&sh.cand_count, hcnt);
-  base = __builtin_amdgcn_readfirstlane(base);
-  for (int h0 = 0; h0 < hcnt; h0 += 64) {
-    const int h = h0 + int(lane);
-    if (h < hcnt && base + h < cap) {
-      const uint32_t g = hitlist[h];
-      const uint32_t slot = g / (2 * E), j = g % (2 * E);
-      const uint2 vi = ring_vidx[slot];
-      const uint32_t idx = head + (j < E ? vi.x : vi.y) * E + (j % E);
-      cand[base + h] = make_cand(ring_elem<T>(bytes, g), idx);
-    }
-  }
+  (void)lost;      // more candidates than `cap` show in sh.cand_count, which the caller checks
 }
 
 template <typename T> __device__ __forceinline__ float vec_max(const float (&v)[ElemTraits<T>::kPerVec]);
@@ -361,9 +358,8 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
   static_assert(kBatch == 4, "the pass handles a batch as two pairs of tiles");
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ TruncateShared sh;
-  RingPair* ring_all = reinterpret_cast<RingPair*>(dyn_lds);
-  uint2* ring_vidx_all = reinterpret_cast<uint2*>(dyn_lds + NW * kRing * 32);
-  uint16_t* hitlist_all = reinterpret_cast<uint16_t*>(dyn_lds + NW * kRing * 40);
+  uint4* ring_all = reinterpret_cast<uint4*>(dyn_lds);
+  uint32_t* ring_vidx_all = reinterpret_cast<uint32_t*>(dyn_lds + NW * kRing * 16);
   uint32_t* tables = reinterpret_cast<uint32_t*>(dyn_lds);          // 3 x 256 entries, aliasing the rings
   uint64_t* cand = reinterpret_cast<uint64_t*>(dyn_lds + p.ring_bytes);
   // sort scratch: what is left of the ring space behind the tables, or (if that is too small for the
@@ -486,18 +482,17 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
       };
       int wave_cnt = 0;                                // pairs parked in this wave's ring
       int lost = 0;
-      RingPair* ring = ring_all + wave * kRing;
-      uint2* ring_vidx = ring_vidx_all + wave * kRing;
-      uint16_t* hitlist = hitlist_all + wave * kHitList;
+      uint4* ring = ring_all + wave * kRing;
+      uint32_t* ring_vidx = ring_vidx_all + wave * kRing;
       const uint32_t head = uint32_t(rs.head);
 
-      // Two vectors at a time: their exp2 terms go to the partial sums; if any of their elements is
-      // above tau0 the pair is parked in the ring, which is expanded when it is half full.
+      // Two vectors at a time: their exp2 terms go to the partial sums; a vector with an element above
+      // tau0 is parked in the ring, which is expanded when it is a third full.
       auto process_pair = [&](const uint4& w0, const uint4& w1, uint32_t vidx0, uint32_t vidx1) {
         float a[E], b[E];
         unpack<T>(w0, a);
         unpack<T>(w1, b);
-        const float mx = fmaxf(vec_max<T>(a), vec_max<T>(b));
+        const bool hit_a = vec_max<T>(a) > tau0, hit_b = vec_max<T>(b) > tau0;
 #pragma unroll
         for (int e = 0; e < E; e += 4) {
           acc0 += fast_exp2(__builtin_fmaf(a[e + 0], k2, neg_c));
@@ -512,22 +507,20 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
           acc2 += fast_exp2(__builtin_fmaf(b[e + 2], k2, neg_c));
           acc3 += fast_exp2(__builtin_fmaf(b[e + 3], k2, neg_c));
         }
-        const bool hit = mx > tau0;
-        const uint64_t mask = ballot(hit);
-        if (mask != 0) {
-          const int pos = wave_cnt + lanes_below(mask);
-          if (hit) {
-            if (pos < kRing) {
-              ring[pos].w[0] = w0;
-              ring[pos].w[1] = w1;
-              ring_vidx[pos] = make_uint2(vidx0, vidx1);
-            } else {
-              lost = 1;
-            }
+        const uint64_t mask_a = ballot(hit_a), mask_b = ballot(hit_b);
+        if ((mask_a | mask_b) != 0) {
+          const int n_a = __popcll(mask_a);
+          const int pos_a = wave_cnt + lanes_below(mask_a);
+          const int pos_b = wave_cnt + n_a + lanes_below(mask_b);
+          if (hit_a) {
+            if (pos_a < kRing) { ring[pos_a] = w0; ring_vidx[pos_a] = vidx0; } else lost = 1;
           }
-          wave_cnt += __popcll(mask);
+          if (hit_b) {
+            if (pos_b < kRing) { ring[pos_b] = w1; ring_vidx[pos_b] = vidx1; } else lost = 1;
+          }
+          wave_cnt += n_a + __popcll(mask_b);
           if (wave_cnt > kRing / 3) {                  // wave-uniform
-            expand_ring<T>(ring, ring_vidx, hitlist, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh, lost);
+            expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh, lost);
             wave_cnt = 0;
           }
         }
@@ -568,7 +561,7 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
         process_pair(d[0], d[1], v0, v1);
         flush();
       }
-      expand_ring<T>(ring, ring_vidx, hitlist, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh, lost);
+      expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh, lost);
       if (lost) sh.overflow = 1;
       // edge elements (row not 16-byte aligned, or V not a whole number of vectors)
       if (tid < n_edge) {
