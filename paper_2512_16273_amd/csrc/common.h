@@ -101,45 +101,72 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
   return __builtin_amdgcn_mbcnt_hi(uint32_t(mask >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(mask), 0));
 }
 
-__device__ __forceinline__ double shfl_xor_f64(double v, int m) {
-  int lo = __double2loint(v), hi = __double2hiint(v);
-  lo = __shfl_xor(lo, m, 64); hi = __shfl_xor(hi, m, 64);
-  return __hiloint2double(hi, lo);
-}
-__device__ __forceinline__ double shfl_up_f64(double v, int d) {
-  int lo = __double2loint(v), hi = __double2hiint(v);
-  lo = __shfl_up(lo, d, 64); hi = __shfl_up(hi, d, 64);
-  return __hiloint2double(hi, lo);
-}
 __device__ __forceinline__ double shfl_f64(double v, int src) {
   int lo = __double2loint(v), hi = __double2hiint(v);
   lo = __shfl(lo, src, 64); hi = __shfl(hi, src, 64);
   return __hiloint2double(hi, lo);
 }
 
-__device__ __forceinline__ double wave_sum_f64(double v) {
-#pragma unroll
-  for (int m = 32; m > 0; m >>= 1) v += shfl_xor_f64(v, m);
+// Cross-lane moves on the VALU's data-parallel-primitive path (no LDS round trip).  A lane whose source lies
+// outside its row of 16, or that the row / bank mask leaves out, gets `old`.  Controls used here:
+// row_shr:n = 0x110 + n (lane i reads lane i - n of its row), row_bcast:15 = 0x142 (lane 15 of every row to
+// the whole next row), row_bcast:31 = 0x143 (lane 31 to rows 2 and 3).
+template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF>
+__device__ __forceinline__ int dpp_i32(int old, int v) {
+  return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, BANK_MASK, false);
+}
+template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF>
+__device__ __forceinline__ double dpp_f64(double old, double v) {
+  const int lo = dpp_i32<CTRL, ROW_MASK, BANK_MASK>(__double2loint(old), __double2loint(v));
+  const int hi = dpp_i32<CTRL, ROW_MASK, BANK_MASK>(__double2hiint(old), __double2hiint(v));
+  return __hiloint2double(hi, lo);
+}
+// Inclusive scan over the 64 lanes of a wave with an associative operation `op` whose identity is `id`:
+// four steps inside every row of 16, then the row totals are carried into the later rows.  Lane 63 ends up
+// with the reduction over the wave.
+template <typename Op> __device__ __forceinline__ int wave_scan_i32(int v, int id, Op op) {
+  v = op(v, dpp_i32<0x111>(id, v));
+  v = op(v, dpp_i32<0x112>(id, v));
+  v = op(v, dpp_i32<0x114>(id, v));
+  v = op(v, dpp_i32<0x118>(id, v));
+  v = op(v, dpp_i32<0x142, 0xA>(id, v));
+  v = op(v, dpp_i32<0x143, 0xC>(id, v));
   return v;
 }
-__device__ __forceinline__ float wave_max_f32(float v) {
-#pragma unroll
-  for (int m = 32; m > 0; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+template <typename Op> __device__ __forceinline__ double wave_scan_f64(double v, double id, Op op) {
+  v = op(v, dpp_f64<0x111>(id, v));
+  v = op(v, dpp_f64<0x112>(id, v));
+  v = op(v, dpp_f64<0x114>(id, v));
+  v = op(v, dpp_f64<0x118>(id, v));
+  v = op(v, dpp_f64<0x142, 0xA>(id, v));
+  v = op(v, dpp_f64<0x143, 0xC>(id, v));
   return v;
+}
+__device__ __forceinline__ int last_lane_i32(int v) { return __builtin_amdgcn_readlane(v, 63); }
+__device__ __forceinline__ double last_lane_f64(double v) {
+  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 63), __builtin_amdgcn_readlane(__double2loint(v), 63));
+}
+
+__device__ __forceinline__ int wave_incl_scan_i32(int v) { return wave_scan_i32(v, 0, [](int a, int b) { return a + b; }); }
+__device__ __forceinline__ double wave_incl_scan_f64(double v) {
+  return wave_scan_f64(v, 0.0, [](double a, double b) { return a + b; });
+}
+// Reductions over a wave; every lane gets the result.
+__device__ __forceinline__ double wave_sum_f64(double v) { return last_lane_f64(wave_incl_scan_f64(v)); }
+__device__ __forceinline__ int wave_sum_i32(int v) { return last_lane_i32(wave_incl_scan_i32(v)); }
+__device__ __forceinline__ float wave_max_f32(float v) {
+  // on the bit patterns: the maximum of NaN-free floats through fmaxf, carried as ints by the moves
+  const int r = wave_scan_i32(__float_as_int(v), __float_as_int(-INFINITY),
+                              [](int a, int b) { return __float_as_int(fmaxf(__int_as_float(a), __int_as_float(b))); });
+  return __int_as_float(last_lane_i32(r));
 }
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-#pragma unroll
-  for (int m = 32; m > 0; m >>= 1) {
-    uint32_t o = uint32_t(__shfl_xor(int(v), m, 64));
-    v = o > v ? o : v;
-  }
-  return v;
+  return uint32_t(last_lane_i32(wave_scan_i32(int(v), 0, [](int a, int b) { return int(uint32_t(a) > uint32_t(b) ? uint32_t(a) : uint32_t(b)); })));
 }
-__device__ __forceinline__ int wave_sum_i32(int v) {
-#pragma unroll
-  for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m, 64);
-  return v;
+__device__ __forceinline__ int wave_max_i32(int v) {
+  return last_lane_i32(wave_scan_i32(v, int(0x80000000), [](int a, int b) { return a > b ? a : b; }));
 }
+__device__ __forceinline__ int wave_or_i32(int v) { return last_lane_i32(wave_scan_i32(v, 0, [](int a, int b) { return a | b; })); }
 
 // Small per-block scratch for reductions and scans; one instance lives in static LDS.
 // `NW` is the number of waves of the workgroup that calls the helpers.
@@ -182,8 +209,7 @@ template <int NW> __device__ __forceinline__ int block_sum_i32(int v, BlockScrat
 }
 
 template <int NW> __device__ __forceinline__ int block_max_i32(int v, BlockScratch& s) {
-#pragma unroll
-  for (int m = 32; m > 0; m >>= 1) { const int o = __shfl_xor(v, m, 64); v = o > v ? o : v; }
+  v = wave_max_i32(v);
   __syncthreads();
   if (lane_id() == 0) s.i[wave_id()] = v;
   __syncthreads();
@@ -194,8 +220,7 @@ template <int NW> __device__ __forceinline__ int block_max_i32(int v, BlockScrat
 }
 
 template <int NW> __device__ __forceinline__ int block_or_i32(int v, BlockScratch& s) {
-#pragma unroll
-  for (int m = 32; m > 0; m >>= 1) v |= __shfl_xor(v, m, 64);
+  v = wave_or_i32(v);
   __syncthreads();
   if (lane_id() == 0) s.i[wave_id()] = v;
   __syncthreads();
@@ -207,12 +232,7 @@ template <int NW> __device__ __forceinline__ int block_or_i32(int v, BlockScratc
 
 // Block-wide exclusive scans in thread order; `total` receives the sum over the block.
 template <int NW> __device__ __forceinline__ double block_excl_scan_f64(double v, BlockScratch& s, double& total) {
-  double inc = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    double up = shfl_up_f64(inc, d);
-    if (lane_id() >= d) inc += up;
-  }
+  const double inc = wave_incl_scan_f64(v);
   __syncthreads();
   if (lane_id() == 63) s.d[wave_id()] = inc;
   __syncthreads();
@@ -226,12 +246,7 @@ template <int NW> __device__ __forceinline__ double block_excl_scan_f64(double v
   return base + inc - v;
 }
 template <int NW> __device__ __forceinline__ int block_excl_scan_i32(int v, BlockScratch& s, int& total) {
-  int inc = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    int up = __shfl_up(inc, d, 64);
-    if (lane_id() >= d) inc += up;
-  }
+  const int inc = wave_incl_scan_i32(v);
   __syncthreads();
   if (lane_id() == 63) s.i[wave_id()] = inc;
   __syncthreads();

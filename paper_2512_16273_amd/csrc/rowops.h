@@ -744,11 +744,8 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const
             if (run > target && first_pass == 0x7FFFFFFF) first_pass = tid * kPerT + q;
           }
         }
-#pragma unroll
-        for (int m = 32; m > 0; m >>= 1) {
-          const int o = __shfl_xor(first_pass, m, 64); first_pass = o < first_pass ? o : first_pass;
-          const int q = __shfl_xor(last_mass, m, 64); last_mass = q > last_mass ? q : last_mass;
-        }
+        first_pass = -wave_max_i32(-first_pass);      // the smallest over the wave (0x7FFFFFFF = none)
+        last_mass = wave_max_i32(last_mass);
         __syncthreads();
         if (lane_id() == 0) { sh.red.i[wave_id()] = first_pass; sh.red.i[8 + wave_id()] = last_mass; }
         __syncthreads();

@@ -42,13 +42,8 @@ __global__ __launch_bounds__(64) void sample_kernel(const SampleParams p) {
 #pragma unroll
     for (int r = 0; r < kSamplePer; ++r) local += w[r];
     // inclusive scan of the lane totals
-    double inc = local;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      double up = shfl_up_f64(inc, d);
-      if (lane >= d) inc += up;
-    }
-    const double total = shfl_f64(inc, 63);
+    const double inc = wave_incl_scan_f64(local);
+    const double total = last_lane_f64(inc);
     int slot = -1;
     if (total > 0.0) {
       const double target = double(p.u[size_t(row) * p.n_samples + c]) * total;
@@ -65,12 +60,7 @@ __global__ __launch_bounds__(64) void sample_kernel(const SampleParams p) {
       }
       slot = wave_sum_i32(not_above);   // prefix sums are non-decreasing: first bucket above the target
       if (slot >= count) {              // only for u >= 1: the last bucket that has weight
-#pragma unroll
-        for (int m = 32; m > 0; m >>= 1) {
-          int o = __shfl_xor(last_pos, m, 64);
-          last_pos = o > last_pos ? o : last_pos;
-        }
-        slot = last_pos;
+        slot = wave_max_i32(last_pos);
       }
       if (p.without_replacement) {
 #pragma unroll

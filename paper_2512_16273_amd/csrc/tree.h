@@ -251,8 +251,7 @@ __global__ __launch_bounds__(64) void tree_walk_kernel(const TreeParams p) {
   const int lane = threadIdx.x;
   int st = 0;
   for (int n = lane; n < p.n_int; n += 64) st |= p.node_status[b * p.n_int + n];
-#pragma unroll
-  for (int m = 32; m > 0; m >>= 1) st |= __shfl_xor(st, m, 64);
+  st = wave_or_i32(st);
   if (lane == 0) {
     int node = 0, layer = 0, len = 0;
     int32_t* seq = p.out_seq + size_t(b) * (p.depth + 1);

@@ -319,13 +319,8 @@ __device__ __forceinline__ void expand_ring(const uint4* ring, const uint32_t* r
 #pragma unroll
       for (int e = 0; e < E; ++e) v[e] = -INFINITY;
     }
-    int incl = cnt;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const int up = __shfl_up(incl, d, 64);
-      if (lane >= d) incl += up;
-    }
-    const int total = __shfl(incl, 63, 64);
+    const int incl = wave_incl_scan_i32(cnt);
+    const int total = last_lane_i32(incl);
     if (total == 0) continue;
     int base = 0;
     if (lane == 0) base = atomicAdd(&sh.cand_count, total);

@@ -132,8 +132,7 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
     int j0 = p.gamma;
     for (int j = lane; j < p.gamma; j += 64)
       if (p.flags[b * p.gamma + j] != 1) { j0 = j; break; }
-#pragma unroll
-    for (int m = 32; m > 0; m >>= 1) { const int o = __shfl_xor(j0, m, 64); j0 = o < j0 ? o : j0; }
+    j0 = -wave_max_i32(-j0);        // the smallest over the wave
     if (lane == 0) { jstar_l = j0; flags_l = 0; }
   }
   double* table = nullptr;
@@ -193,8 +192,7 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
             for (int i = 0; i < kSegVecs; ++i) d[i] = dn[i];
           }
         }
-#pragma unroll
-        for (int m = 32; m > 0; m >>= 1) flags |= __shfl_xor(flags, m, 64);
+        flags = wave_or_i32(flags);
         if (lane == 0 && flags) atomicOr(&flags_l, flags);
         __syncthreads();
         const int fl = flags_l;
@@ -233,8 +231,8 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
             vmax = fmaxf(vmax, v[e]);
           }
         }
-#pragma unroll
-        for (int m = 32; m > 0; m >>= 1) { vmax = fmaxf(vmax, __shfl_xor(vmax, m, 64)); bad |= __shfl_xor(bad, m, 64); }
+        vmax = wave_max_f32(vmax);
+        bad = wave_or_i32(bad);
         if (lane == 0) { run_max[wave] = vmax; if (bad) atomicOr(&flags_l, 4); }
         __syncthreads();
         const int w0 = wave & ~(kSubChunks - 1);
