@@ -302,7 +302,7 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
 // are written there.
 template <typename T>
 __device__ __forceinline__ void expand_ring(const uint4* ring, const uint32_t* ring_vidx, int n, float tau0,
-                                            uint32_t head, uint64_t* cand, int cap, TruncateShared& sh, int& lost) {
+                                            uint32_t head, uint64_t* cand, int cap, TruncateShared& sh) {
   constexpr int E = ElemTraits<T>::kPerVec;
   const int lane = lane_id();
   for (int s0 = 0; s0 < n; s0 += 64) {
@@ -335,7 +335,7 @@ __device__ __forceinline__ void expand_ring(const uint4* ring, const uint32_t* r
       }
     }
   }
-  (void)lost;      // more candidates than `cap` show in sh.cand_count, which the caller checks
+  // more candidates than `cap` show in sh.cand_count, which the caller checks
 }
 
 template <typename T> __device__ __forceinline__ float vec_max(const float (&v)[ElemTraits<T>::kPerVec]);
@@ -476,7 +476,7 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
         acc0 = acc1 = acc2 = acc3 = 0.f;
       };
       int wave_cnt = 0;                                // pairs parked in this wave's ring
-      int lost = 0;
+      bool lost = false;                               // wave-uniform: a ring overflowed
       uint4* ring = ring_all + wave * kRing;
       uint32_t* ring_vidx = ring_vidx_all + wave * kRing;
       const uint32_t head = uint32_t(rs.head);
@@ -508,14 +508,15 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
           const int pos_a = wave_cnt + lanes_below(mask_a);
           const int pos_b = wave_cnt + n_a + lanes_below(mask_b);
           if (hit_a) {
-            if (pos_a < kRing) { ring[pos_a] = w0; ring_vidx[pos_a] = vidx0; } else lost = 1;
+            if (pos_a < kRing) { ring[pos_a] = w0; ring_vidx[pos_a] = vidx0; }
           }
           if (hit_b) {
-            if (pos_b < kRing) { ring[pos_b] = w1; ring_vidx[pos_b] = vidx1; } else lost = 1;
+            if (pos_b < kRing) { ring[pos_b] = w1; ring_vidx[pos_b] = vidx1; }
           }
           wave_cnt += n_a + __popcll(mask_b);
+          lost |= wave_cnt > kRing;                    // some vector found no slot
           if (wave_cnt > kRing / 3) {                  // wave-uniform
-            expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh, lost);
+            expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh);
             wave_cnt = 0;
           }
         }
@@ -556,8 +557,8 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
         process_pair(d[0], d[1], v0, v1);
         flush();
       }
-      expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh, lost);
-      if (lost) sh.overflow = 1;
+      expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh);
+      if (lost && lane == 0) sh.overflow = 1;
       // edge elements (row not 16-byte aligned, or V not a whole number of vectors)
       if (tid < n_edge) {
         const int64_t edge_i = edge_index<T>(rs, tid);
