@@ -53,7 +53,7 @@ class ChainPlan:
                    "status": torch.empty(B, dtype=i32, device=dev)}
         self.ws = torch.empty(tslt.workspace_bytes(tslt.OP_VERIFY, B, G, V, K), dtype=torch.uint8, device=dev)
         self.positions = B * G
-        s = 2 if w.dtype == "bf16" else 4
+        s = 4 if w.dtype == "f32" else 2
         # bytes the method has to move: every draft and target logit once, the sparse representation once out
         # and once in; re-reads (the resampled row) earn no credit
         sparse_w = B * G * K * 12 + B * G * 8
@@ -126,7 +126,7 @@ class TreePlan:
         if len(set(w.expansion)) != 1:
             raise SystemExit("bench.py: the tree workload needs the same number of candidates at every layer")
         self.positions = B * (n_nodes - 1)                 # candidate nodes
-        s = 2 if w.dtype == "bf16" else 4
+        s = 4 if w.dtype == "f32" else 2
         sparse = R * K * 12
         # the verified path needs at most depth + 1 target rows per tree (uniforms are indexed by node, so the
         # nodes off the path never influence the output); every draft row is needed for its candidates
@@ -189,6 +189,7 @@ def main():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--workload", default="large_vocab")
+    ap.add_argument("--dtype", default="", choices=["", "f32", "bf16", "f16"], help="override the workload's logit storage type")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's B (sequences or trees)")
     ap.add_argument("--sets", type=int, default=0, help="independent input sets rotated between steps (default 3; 1 for tree)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -212,6 +213,8 @@ def main():
     w = W.WORKLOADS[args.workload]
     if args.batch > 0:
         w = W.scaled(w, B=args.batch)
+    if args.dtype:
+        w = W.scaled(w, dtype=args.dtype)
     is_tree = len(w.expansion) > 0
     n_sets = args.sets if args.sets > 0 else (1 if is_tree else 3)
     plan = (TreePlan if is_tree else ChainPlan)(w, n_sets, torch, tslt, W, dev)

@@ -20,7 +20,7 @@
  *   - Data-dependent problems never abort.  They set bits in the optional per-row / per-sequence
  *     `status` array (TSLT_ROW_*) and give the defined fallback (count 0, token -1).
  *   - Logit rows are row-major with `row_stride` elements between rows; any alignment of the element
- *     type is accepted.  dtype is fp32 or bf16 (bf16 is widened exactly to fp32 on load).
+ *     type is accepted.  dtype is fp32, bf16 or binary16 (16-bit elements are widened exactly to fp32 on load).
  *   - Temperature (not in the paper): s = fl32(z * fl32(1/T)), one fp32 multiplication per logit.
  *     The SCALED values are what a truncated set carries, so the server needs no draft-side
  *     parameter: q_hat is the plain softmax of the received values.  T must be > 0.
@@ -42,7 +42,8 @@
 extern "C" {
 #endif
 
-typedef enum { TSLT_F32 = 0, TSLT_BF16 = 1, TSLT_F16 = 2 /* payload values only */ } tslt_dtype;
+/* element type of logit rows, and format of travelling values: fp32, bfloat16, IEEE binary16 */
+typedef enum { TSLT_F32 = 0, TSLT_BF16 = 1, TSLT_F16 = 2 } tslt_dtype;
 
 enum {
   TSLT_OK = 0,

@@ -10,6 +10,7 @@ constexpr int kWaves = kBlock / 64;
 constexpr uint32_t kNegInfBits = 0xFF800000u;
 
 struct Bf16 { uint16_t bits; };        // storage tag for bf16 rows
+struct F16 { uint16_t bits; };         // storage tag for binary16 rows
 
 template <typename T> struct ElemTraits;
 template <> struct ElemTraits<float> {
@@ -17,6 +18,10 @@ template <> struct ElemTraits<float> {
   static constexpr int kBytes = 4;
 };
 template <> struct ElemTraits<Bf16> {
+  static constexpr int kPerVec = 8;
+  static constexpr int kBytes = 2;
+};
+template <> struct ElemTraits<F16> {
   static constexpr int kPerVec = 8;
   static constexpr int kBytes = 2;
 };
@@ -36,12 +41,25 @@ template <> __device__ __forceinline__ void unpack<Bf16>(const uint4& w, float (
   v[6] = as_f32(w.w << 16); v[7] = as_f32(w.w & 0xFFFF0000u);
 }
 
+__device__ __forceinline__ float f16_lo(uint32_t w) { return float(__builtin_bit_cast(_Float16, uint16_t(w))); }
+__device__ __forceinline__ float f16_hi(uint32_t w) { return float(__builtin_bit_cast(_Float16, uint16_t(w >> 16))); }
+template <> __device__ __forceinline__ void unpack<F16>(const uint4& w, float (&v)[8]) {
+  v[0] = f16_lo(w.x); v[1] = f16_hi(w.x);
+  v[2] = f16_lo(w.y); v[3] = f16_hi(w.y);
+  v[4] = f16_lo(w.z); v[5] = f16_hi(w.z);
+  v[6] = f16_lo(w.w); v[7] = f16_hi(w.w);
+}
+
 template <typename T> __device__ __forceinline__ uint4 neg_inf_vec();
 template <> __device__ __forceinline__ uint4 neg_inf_vec<float>() {
   return make_uint4(kNegInfBits, kNegInfBits, kNegInfBits, kNegInfBits);
 }
 template <> __device__ __forceinline__ uint4 neg_inf_vec<Bf16>() {
   return make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u);
+}
+
+template <> __device__ __forceinline__ uint4 neg_inf_vec<F16>() {
+  return make_uint4(0xFC00FC00u, 0xFC00FC00u, 0xFC00FC00u, 0xFC00FC00u);
 }
 
 // Scalar load of element i of a row, any alignment of the element type.
@@ -51,6 +69,10 @@ template <> __device__ __forceinline__ float load_elem<float>(const void* row, i
 }
 template <> __device__ __forceinline__ float load_elem<Bf16>(const void* row, int64_t i) {
   return as_f32(uint32_t(reinterpret_cast<const uint16_t*>(row)[i]) << 16);
+}
+
+template <> __device__ __forceinline__ float load_elem<F16>(const void* row, int64_t i) {
+  return f16_lo(reinterpret_cast<const uint16_t*>(row)[i]);
 }
 
 // Order-preserving map fp32 -> uint32 (larger value, larger key).  -0.0 must be folded into +0.0 by

@@ -342,9 +342,11 @@ template <typename T> __device__ __forceinline__ float vec_max(const float (&v)[
 template <> __device__ __forceinline__ float vec_max<float>(const float (&v)[4]) {
   return max3f(max3f(v[0], v[1], v[2]), v[3], v[3]);
 }
-template <> __device__ __forceinline__ float vec_max<Bf16>(const float (&v)[8]) {
+__device__ __forceinline__ float vec_max8(const float (&v)[8]) {
   return max3f(max3f(max3f(v[0], v[1], v[2]), v[3], v[4]), max3f(v[5], v[6], v[7]), v[5]);
 }
+template <> __device__ __forceinline__ float vec_max<Bf16>(const float (&v)[8]) { return vec_max8(v); }
+template <> __device__ __forceinline__ float vec_max<F16>(const float (&v)[8]) { return vec_max8(v); }
 
 template <typename T, int NT>
 __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {

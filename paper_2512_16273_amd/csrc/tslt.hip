@@ -33,7 +33,8 @@ int hip_fail(hipError_t e, const char* what) {
   return fail(TSLT_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-bool valid_dtype(tslt_dtype dt) { return dt == TSLT_F32 || dt == TSLT_BF16; }
+bool valid_dtype(tslt_dtype dt) { return dt == TSLT_F32 || dt == TSLT_BF16 || dt == TSLT_F16; }
+int elem_bytes(tslt_dtype dt) { return dt == TSLT_F32 ? 4 : 2; }
 
 // fl32(1/T), the one scaling constant every side derives the same way
 float reciprocal_temperature(float T) { return float(1.0 / double(T)); }
@@ -44,7 +45,7 @@ constexpr size_t kMaxLds = 160 * 1024;   // LDS of one gfx950 compute unit
 // Launch plan of the truncate kernel: which rank among the per-thread sample maxima gives the
 // threshold, and how large the candidate array has to be.  Returns the bytes of dynamic LDS.
 size_t plan_truncate(tslt_dtype dt, int64_t V, int nt, tslt::TruncateParams& p) {
-  const int E = dt == TSLT_BF16 ? 8 : 4;
+  const int E = 16 / elem_bytes(dt);
   const double G = nt;                                 // per-thread sample maxima
   const int64_t tile = int64_t(nt) * E;
   const int64_t n_tiles = (V + tile - 1) / tile;
@@ -55,7 +56,9 @@ size_t plan_truncate(tslt_dtype dt, int64_t V, int nt, tslt::TruncateParams& p) 
   const double j = f >= 1.0 ? kp + 1.0 : kp + 4.0 * std::sqrt(kp) + 4.0;
   const double jc = G * (1.0 - std::exp(-j / G));      // distinct threads holding the top j
   const int jprime = int(std::ceil(jc + 2.0 * std::sqrt(j > jc ? j - jc : 0.0) + 1.0));
-  p.tau_bits = dt == TSLT_BF16 ? 16 : 20;
+  // every bf16 value is told apart by the leading 16 bits of its fp32 key, every binary16 value (11
+  // significant bits) by the leading 19
+  p.tau_bits = dt == TSLT_BF16 ? 16 : (dt == TSLT_F16 ? 19 : 20);
   p.jprime = 0;
   // candidate capacity: always room for the fallback's 1024 group maxima and for 2 * k_sel records.
   // The sort needs about 1.5 * k_sel records of scratch: the ring space behind the sort's tables if
@@ -122,7 +125,7 @@ static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_
   if (payload != TSLT_F32 && payload != TSLT_BF16 && payload != TSLT_F16) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: unknown payload format %d", int(payload));
   if (rows == 0) return TSLT_OK;
   if (!logits || !out_idx || !out_logit || !out_count) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: null pointer");
-  if (reinterpret_cast<uintptr_t>(logits) % (dt == TSLT_BF16 ? 2 : 4)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: logits not aligned to their element type");
+  if (reinterpret_cast<uintptr_t>(logits) % elem_bytes(dt)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: logits not aligned to their element type");
 
   tslt::TruncateParams p{};
   p.logits = logits; p.rows = rows; p.V = V; p.row_stride = row_stride;
@@ -146,6 +149,9 @@ static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_
   if (dt == TSLT_BF16) {
     if (big_lds && (e = allow_large_lds(&tslt::truncate_kernel<tslt::Bf16, NT>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
     hipLaunchKernelGGL((tslt::truncate_kernel<tslt::Bf16, NT>), grid, block, lds, s, p);
+  } else if (dt == TSLT_F16) {
+    if (big_lds && (e = allow_large_lds(&tslt::truncate_kernel<tslt::F16, NT>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    hipLaunchKernelGGL((tslt::truncate_kernel<tslt::F16, NT>), grid, block, lds, s, p);
   } else {
     if (big_lds && (e = allow_large_lds(&tslt::truncate_kernel<float, NT>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
     hipLaunchKernelGGL((tslt::truncate_kernel<float, NT>), grid, block, lds, s, p);
@@ -252,7 +258,7 @@ static int verify_impl(int phases, const char* name, const void* target_logits, 
   if (!target_logits || !q_idx || !q_logit || !q_count || !draft_tokens || !u_accept || !u_resample ||
       !out_accept_len || !out_tokens)
     return fail(TSLT_ERR_INVALID_ARG, "%s: null pointer", name);
-  if (reinterpret_cast<uintptr_t>(target_logits) % (dt == TSLT_BF16 ? 2 : 4)) return fail(TSLT_ERR_INVALID_ARG, "%s: logits not aligned to their element type", name);
+  if (reinterpret_cast<uintptr_t>(target_logits) % elem_bytes(dt)) return fail(TSLT_ERR_INVALID_ARG, "%s: logits not aligned to their element type", name);
   const size_t need = tslt::verify_workspace_bytes(B, gamma, V, k_cap);
   if (!ws || ws_bytes < need || reinterpret_cast<uintptr_t>(ws) % 256)
     return fail(TSLT_ERR_WORKSPACE, "%s: workspace of %zu bytes, 256-byte aligned, required", name, need);
@@ -267,7 +273,8 @@ static int verify_impl(int phases, const char* name, const void* target_logits, 
   p.status = status;
   tslt::verify_carve_workspace(p, ws);
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  hipError_t e = dt == TSLT_BF16 ? tslt::launch_verify<tslt::Bf16>(p, s, phases) : tslt::launch_verify<float>(p, s, phases);
+  hipError_t e = dt == TSLT_BF16 ? tslt::launch_verify<tslt::Bf16>(p, s, phases)
+                 : dt == TSLT_F16 ? tslt::launch_verify<tslt::F16>(p, s, phases) : tslt::launch_verify<float>(p, s, phases);
   if (e != hipSuccess) return hip_fail(e, name);
   return TSLT_OK;
 }
@@ -323,7 +330,7 @@ int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_
   if (B == 0) return TSLT_OK;
   if (!target_logits || !q_idx || !q_logit || !q_count || !cand_tokens || !u_accept || !u_resample || !out_seq || !out_len)
     return fail(TSLT_ERR_INVALID_ARG, "%s: null pointer", name);
-  if (reinterpret_cast<uintptr_t>(target_logits) % (dt == TSLT_BF16 ? 2 : 4)) return fail(TSLT_ERR_INVALID_ARG, "%s: logits not aligned to their element type", name);
+  if (reinterpret_cast<uintptr_t>(target_logits) % elem_bytes(dt)) return fail(TSLT_ERR_INVALID_ARG, "%s: logits not aligned to their element type", name);
   const size_t need = tslt::tree_workspace_bytes(B, n_nodes, V, all_nodes);
   if (!ws || ws_bytes < need || reinterpret_cast<uintptr_t>(ws) % 256)
     return fail(TSLT_ERR_WORKSPACE, "%s: workspace of %zu bytes, 256-byte aligned, required", name, need);
@@ -337,7 +344,8 @@ int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_
   p.out_ratio = out_ratio; p.out_beta = out_beta; p.status = status;
   tslt::tree_carve_workspace(p, ws);
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-  hipError_t e = dt == TSLT_BF16 ? tslt::launch_verify_tree<tslt::Bf16>(p, s) : tslt::launch_verify_tree<float>(p, s);
+  hipError_t e = dt == TSLT_BF16 ? tslt::launch_verify_tree<tslt::Bf16>(p, s)
+                 : dt == TSLT_F16 ? tslt::launch_verify_tree<tslt::F16>(p, s) : tslt::launch_verify_tree<float>(p, s);
   if (e != hipSuccess) return hip_fail(e, name);
   return TSLT_OK;
 }

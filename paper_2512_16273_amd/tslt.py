@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtslt.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 OP_TRUNCATE, OP_SAMPLE, OP_VERIFY, OP_VERIFY_TREE, OP_VERIFY_TREE_PATH = 0, 1, 2, 3, 4
 ROW_NONFINITE, ROW_EMPTY, ROW_TOKEN_NOT_IN_SET, ROW_EXACT_PATH = 1, 2, 4, 256
 MAX_K_CAP = 1024
@@ -84,6 +84,8 @@ def _dtype_code(t: torch.Tensor) -> int:
         return F32
     if t.dtype == torch.bfloat16:
         return BF16
+    if t.dtype == torch.float16:
+        return F16
     raise TsltError(f"unsupported logits dtype {t.dtype}")
 
 

@@ -36,7 +36,7 @@ class Workload:
     name: str
     B: int
     V: int
-    dtype: str                 # "f32" | "bf16"
+    dtype: str                 # "f32" | "bf16" | "f16"
     sigma: float               # std of the Gaussian part of a base row
     noise_t: float             # std of target - draft noise
     T: float                   # temperature (draft and target)
@@ -75,7 +75,7 @@ def scaled(w: Workload, **kw) -> Workload:
 
 
 def torch_dtype(name: str) -> torch.dtype:
-    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+    return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[name]
 
 
 def _generator(device, seed: int, config_id: int, stream: int) -> torch.Generator:

@@ -18,7 +18,7 @@ RTOL = 1e-5
 def to_np(t):
     if isinstance(t, torch.Tensor):
         t = t.detach()
-        if t.dtype == torch.bfloat16:
+        if t.dtype in (torch.bfloat16, torch.float16):
             t = t.float()
         return t.cpu().numpy()
     return np.asarray(t)

@@ -32,6 +32,8 @@ def oracle_for(w, tree, renormalised_rule=False):
     ("f32-iid", dict(B=3, V=7001, expansion=(2, 2, 2), top_k=6, k_cap=8, without_replacement=False)),
     ("bf16-44", dict(B=2, V=20011, dtype="bf16", expansion=(4, 4), top_k=32, k_cap=32, T=0.9)),
     ("bf16-topp", dict(B=2, V=30000, dtype="bf16", expansion=(2, 3), top_k=0, top_p=0.9, k_cap=256, T=0.8)),
+    ("f16-topp", dict(B=2, V=30000, dtype="f16", expansion=(2, 3), top_k=0, top_p=0.9, k_cap=256, T=0.8)),
+    ("f16-44", dict(B=2, V=20011, dtype="f16", expansion=(4, 4), top_k=32, k_cap=32, T=0.9)),
     ("f32-deep", dict(B=2, V=3000, expansion=(1, 2, 1, 2, 1, 2), top_k=4, k_cap=4)),
 ])
 def test_tree_matches_oracle(tslt, name, kw):

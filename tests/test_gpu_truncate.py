@@ -26,9 +26,13 @@ def rows_like(w, n_rows, seed):
     ("bf16-k1", 9000, 4, 1.0, 1, 0.0, 1),
     ("f32-tinyV", 10, 3, 1.0, 0, 0.0, 16),                # K > V
     ("bf16-smallV", 777, 5, 1.3, 64, 0.0, 64),
+    ("f16-odd", 20011, 37, 0.8, 64, 0.0, 64),             # binary16 rows, every 2-byte phase
+    ("f16-topp", 32000, 24, 0.8, 0, 0.95, 256),
+    ("f16-k1024", 70000, 6, 1.0, 0, 0.99, 1024),
+    ("f16-smallV", 777, 5, 1.3, 64, 0.0, 64),
 ])
 def test_truncate_matches_oracle(tslt, name, V, rows, T, top_k, top_p, k_cap):
-    w = W.scaled(W.WORKLOADS["chain_topk"], V=V, dtype="f32" if name.startswith("f32") else "bf16")
+    w = W.scaled(W.WORKLOADS["chain_topk"], V=V, dtype=name.split("-")[0])
     z = rows_like(w, rows, 3)
     out = tslt.truncate(z, T, top_k, top_p, k_cap)
     torch.cuda.synchronize()
@@ -63,7 +67,7 @@ def test_truncate_degenerate_rows(tslt):
     rows[9, 1::2] = -0.0                                       # signed zeros are one value
     rows[10, :3000] = -float("inf")
     rows[11] = base[11].abs() * -50                            # huge spread
-    for dt in (torch.float32, torch.bfloat16):
+    for dt in (torch.float32, torch.bfloat16, torch.float16):
         z = rows.to(dt).to(DEV)
         for (k, p, cap) in ((16, 0.0, 16), (0, 0.9, 256), (300, 0.0, 512)):
             out = tslt.truncate(z, 0.7, k, p, cap)
@@ -113,11 +117,12 @@ def test_sample_matches_oracle(tslt, wo):
     ("f32-topk-3", 5000, 9, 1.0, 16, 0.0, 16, 3),
     ("bf16-k1024-2", 70000, 6, 1.0, 0, 0.999, 1024, 2),
     ("bf16-k3-16", 9000, 5, 1.0, 3, 0.0, 4, 16),
+    ("f16-topp-2", 32000, 12, 0.8, 0, 0.95, 256, 2),
 ])
 def test_truncate_sample_in_one_launch(tslt, name, V, rows, T, top_k, top_p, k_cap, n):
     """tslt_truncate_sample: the truncation against the oracle as for tslt_truncate; the draws against the
     oracle's sampling from the very sets the call returned, and against tslt_sample on those sets."""
-    w = W.scaled(W.WORKLOADS["chain_topk"], V=V, dtype="f32" if name.startswith("f32") else "bf16")
+    w = W.scaled(W.WORKLOADS["chain_topk"], V=V, dtype=name.split("-")[0])
     z = rows_like(w, rows, 21)
     u = W.uniforms((rows, n), 9, 2, 3, DEV)
     out = tslt.truncate(z, T, top_k, top_p, k_cap, u=u)

@@ -29,6 +29,9 @@ def run_verify_from_oracle_inputs(tslt, w, chain, ref):
     ("bf16-topp", "chain_topp", dict(B=10)),
     ("bf16-k1024", "stress", dict(B=3, gamma=4, V=70000)),
     ("bf16-one-segment", "chain_topk", dict(B=5, V=2000, gamma=2)),
+    ("f16-topk", "chain_topk", dict(B=12, V=20011, dtype="f16")),
+    ("f16-topp", "chain_topp", dict(B=10, dtype="f16")),
+    ("f16-k1024", "stress", dict(B=3, gamma=4, V=70000, dtype="f16")),
 ])
 def test_verify_matches_oracle(tslt, name, base, kw):
     w = W.scaled(W.WORKLOADS[base], **kw)
