@@ -43,19 +43,44 @@ struct VerifyShared {
   double sub_val[kSubChunks];      // level 2: mass of every run of the chosen segment
 };
 
-// A table of exp(s) for every bf16 logit z with 2^-6 <= |z| < 2^7, s = fl32(z / T): the fp64 sums over
-// a bf16 row then cost one LDS read per element instead of an fp64 exponential.  With the 16 bits of an
-// element rotated left by one (sign in bit 0), entry 1 + (rotated - 2*kTabLo) holds its value; entries 0
-// and kTabEntries + 1 hold NaN and stand for everything below and above the table's domain (tiny, huge,
-// -inf, NaN), which is evaluated directly.  Terms are referenced to 0 rather than to the row maximum,
-// which is safe while |s| <= kTabMaxS; a segment that holds a larger |s| is redone by the
-// maximum-referenced path.
-constexpr int kTabLo = (127 - 6) << 7;
-constexpr int kTabSpan = 13 << 7;
-constexpr int kTabEntries = 2 * kTabSpan;
-constexpr size_t kTabBytes = size_t(kTabEntries + 2) * sizeof(double);
+// A table of exp(s), s = fl32(z / T), for every 16-bit logit z of a magnitude range that holds the bulk of
+// a row: the fp64 sums over the row then cost one LDS read per element instead of an fp64 exponential.
+//   bfloat16  2^-6 <= |z| < 2^7   3328 values, 26 KB
+//   binary16  2^-2 <= |z| < 2^5  14336 values, 112 KB
+// With the 16 bits of an element rotated left by one (sign in bit 0), entry 1 + (rotated - 2*kLo) holds
+// its value; entries 0 and kEntries + 1 hold NaN and stand for everything below and above the table's
+// domain (tiny, huge, -inf, NaN), which is evaluated directly.  Terms are referenced to 0 rather than to
+// the row maximum, which is safe while |s| <= kTabMaxS; a segment that holds a larger |s| is redone by
+// the maximum-referenced path.
 constexpr float kTabMaxS = 600.0f;
-inline bool exp_table_usable(float rT) { return 128.0f * rT <= kTabMaxS; }
+template <typename T> struct ExpTab {
+  static constexpr bool kHas = false;
+  static constexpr size_t kBytes = 0;
+};
+template <> struct ExpTab<Bf16> {
+  static constexpr bool kHas = true;
+  static constexpr int kLo = (127 - 6) << 7;       // bits of the smallest magnitude covered
+  static constexpr int kSpan = 13 << 7;            // magnitudes covered
+  static constexpr int kEntries = 2 * kSpan;
+  static constexpr size_t kBytes = size_t(kEntries + 2) * sizeof(double);
+  static constexpr float kMaxAbs = 128.0f;
+  static constexpr uint32_t kInf = 0x7F80u;
+  static __device__ __forceinline__ float widen(uint32_t bits) { return __uint_as_float(bits << 16); }
+};
+template <> struct ExpTab<F16> {
+  static constexpr bool kHas = true;
+  static constexpr int kLo = (15 - 2) << 10;
+  static constexpr int kSpan = 7 << 10;
+  static constexpr int kEntries = 2 * kSpan;
+  static constexpr size_t kBytes = size_t(kEntries + 2) * sizeof(double);
+  static constexpr float kMaxAbs = 32.0f;
+  static constexpr uint32_t kInf = 0x7C00u;
+  static __device__ __forceinline__ float widen(uint32_t bits) { return f16_lo(bits); }
+};
+template <typename T> inline bool exp_table_usable(float rT) {
+  if constexpr (ExpTab<T>::kHas) return ExpTab<T>::kMaxAbs * rT <= kTabMaxS;
+  return false;
+}
 
 // Workgroups of a sweep launch: a few per compute unit, each looping over its share of the segments.
 inline int64_t sweep_grid_limit() {
@@ -66,48 +91,58 @@ inline int64_t sweep_grid_limit() {
   return int64_t(cus) * 4;
 }
 
-__device__ __forceinline__ double exp_table_entry(int i, float rT) {
-  if (i < 1 || i > kTabEntries) return __longlong_as_double(0x7FF8000000000000ll);
+template <typename T> __device__ __forceinline__ double exp_table_entry(int i, float rT) {
+  using TB = ExpTab<T>;
+  if (i < 1 || i > TB::kEntries) return __longlong_as_double(0x7FF8000000000000ll);
   const int j = i - 1;
-  const uint32_t bits = (uint32_t(j & 1) << 15) | uint32_t(kTabLo + (j >> 1));
-  return exp64(double(__fmul_rn(__uint_as_float(bits << 16), rT)));
+  const uint32_t bits = (uint32_t(j & 1) << 15) | uint32_t(TB::kLo + (j >> 1));
+  return exp64(double(__fmul_rn(TB::widen(bits), rT)));
 }
 // Fills the table with all `threads` threads of the workgroup; the caller synchronises.
-__device__ __forceinline__ void build_exp_table(double* table, float rT, int threads) {
-  for (int i = threadIdx.x; i < kTabEntries + 2; i += threads) table[i] = exp_table_entry(i, rT);
+template <typename T> __device__ __forceinline__ void build_exp_table(double* table, float rT, int threads) {
+  for (int i = threadIdx.x; i < ExpTab<T>::kEntries + 2; i += threads) table[i] = exp_table_entry<T>(i, rT);
 }
 
-// exp(s) of one bf16 element given by its 16 bits, for the elements the table does not cover; -1 for
+// exp(s) of one 16-bit element given by its bits, for the elements the table does not cover; -1 for
 // NaN or +inf, -2 for a value that needs the maximum-referenced path
-__device__ __noinline__ double exp_term_bf16(uint32_t b, float rT) {
+template <typename T> __device__ __noinline__ double exp_term_16(uint32_t b, float rT) {
+  using TB = ExpTab<T>;
   const uint32_t m = b & 0x7FFFu;
-  if (m > 0x7F80u || b == 0x7F80u) return -1.0;
-  if (b == 0xFF80u) return 0.0;                                     // -inf: probability 0
-  const float s = __fmul_rn(__uint_as_float(b << 16), rT);
+  if (m > TB::kInf || b == TB::kInf) return -1.0;
+  if (b == (0x8000u | TB::kInf)) return 0.0;                        // -inf: probability 0
+  const float s = __fmul_rn(TB::widen(b), rT);
   if (fabsf(s) > kTabMaxS) return -2.0;
   return exp64(double(s));
 }
 
-// Sum of exp(s) over the 8 bf16 elements of a vector through the table.  The index arithmetic runs on
-// both halves of a 32-bit word at once (16-bit lanes: rotate, saturating subtract, minimum, scale by 8).
-// An element outside the table's domain reads a NaN entry, which shows in the sum; the vector is then
-// redone element by element.
+// Sum of exp(s) over the 8 elements of a 16-bit vector through the table.  The index arithmetic runs on
+// both halves of a 32-bit word at once (16-bit lanes: rotate, saturating subtract, minimum).  An element
+// outside the table's domain reads a NaN entry, which shows in the sum; the vector is then redone
+// element by element.
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+template <typename T>
 __device__ __forceinline__ double table_vec_sum(const uint4& d, const double* table, float rT, int& flags) {
+  using TB = ExpTab<T>;
   const uint32_t w[4] = {d.x, d.y, d.z, d.w};
-  const char* tb = reinterpret_cast<const char*>(table);
-  const ushort2_t base = {uint16_t(2 * kTabLo - 1), uint16_t(2 * kTabLo - 1)};
-  const ushort2_t top = {uint16_t(kTabEntries + 1), uint16_t(kTabEntries + 1)};
-  const ushort2_t three = {3, 3};
+  const ushort2_t base = {uint16_t(2 * TB::kLo - 1), uint16_t(2 * TB::kLo - 1)};
+  const ushort2_t top = {uint16_t(TB::kEntries + 1), uint16_t(TB::kEntries + 1)};
   double s0 = 0.0, s1 = 0.0;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     const uint32_t rot = ((w[k] << 1) & 0xFFFEFFFEu) | ((w[k] >> 15) & 0x00010001u);
     ushort2_t i2 = __builtin_elementwise_sub_sat(__builtin_bit_cast(ushort2_t, rot), base);
-    i2 = __builtin_elementwise_min(i2, top) << three;
-    const uint32_t off = __builtin_bit_cast(uint32_t, i2);
-    s0 += *reinterpret_cast<const double*>(tb + (off & 0xFFFFu));
-    s1 += *reinterpret_cast<const double*>(tb + (off >> 16));
+    i2 = __builtin_elementwise_min(i2, top);
+    if constexpr (TB::kBytes <= 65536) {      // byte offsets fit the 16-bit lanes
+      const ushort2_t three = {3, 3};
+      const uint32_t off = __builtin_bit_cast(uint32_t, i2 << three);
+      const char* tb = reinterpret_cast<const char*>(table);
+      s0 += *reinterpret_cast<const double*>(tb + (off & 0xFFFFu));
+      s1 += *reinterpret_cast<const double*>(tb + (off >> 16));
+    } else {
+      const uint32_t ix = __builtin_bit_cast(uint32_t, i2);
+      s0 += table[ix & 0xFFFFu];
+      s1 += table[ix >> 16];
+    }
   }
   double s = s0 + s1;
   if (s != s) {
@@ -115,11 +150,11 @@ __device__ __forceinline__ double table_vec_sum(const uint4& d, const double* ta
 #pragma unroll 1
     for (int e = 0; e < 8; ++e) {
       const uint32_t b = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-      const uint32_t r = (b & 0x7FFFu) - uint32_t(kTabLo);
+      const uint32_t r = (b & 0x7FFFu) - uint32_t(TB::kLo);
       double t = 0.0;
-      if (r < uint32_t(kTabSpan)) t = table[1 + r * 2 + (b >> 15)];
+      if (r < uint32_t(TB::kSpan)) t = table[1 + r * 2 + (b >> 15)];
       else {
-        t = exp_term_bf16(b, rT);
+        t = exp_term_16<T>(b, rT);
         if (t < 0.0) { flags |= int(-t); t = 0.0; }
       }
       s += t;
@@ -380,7 +415,7 @@ __device__ __forceinline__ void sweep_group(const void* row, const RowSplit& rs,
   const int seg0 = group * kGroupSegs;
   const int n_here = n_seg_row - seg0 < kGroupSegs ? n_seg_row - seg0 : kGroupSegs;   // may be <= 0
   bool direct = n_here > 0;
-  if constexpr (std::is_same<T, Bf16>::value) {
+  if constexpr (ExpTab<T>::kHas) {
     if (table != nullptr && n_here > 0) {
       int flags = 0;
       uint4 d[kSegVecs], dn[kSegVecs];
@@ -393,7 +428,7 @@ __device__ __forceinline__ void sweep_group(const void* row, const RowSplit& rs,
           double run = 0.0;
 #pragma unroll
           for (int i = 0; i < kSegVecs; ++i)
-            if (vbase + i * 64 < rs.nvec) run += table_vec_sum(d[i], table, rT, flags);
+            if (vbase + i * 64 < rs.nvec) run += table_vec_sum<T>(d[i], table, rT, flags);
           const double run_sum = wave_sum_f64(run);
           if (lane_id() == 0) {
             subs[size_t(seg0 + k) * kSubChunks + wave_id()] = run_sum;

@@ -276,10 +276,12 @@ __global__ __launch_bounds__(kBlock) void tree_sweep_kernel(const TreeParams p) 
   __shared__ VerifyShared sh;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   double* table = nullptr;
-  if (std::is_same<T, Bf16>::value && p.use_table) {
-    table = reinterpret_cast<double*>(dyn_lds);
-    build_exp_table(table, p.rT, kBlock);
-    __syncthreads();
+  if constexpr (ExpTab<T>::kHas) {
+    if (p.use_table) {
+      table = reinterpret_cast<double*>(dyn_lds);
+      build_exp_table<T>(table, p.rT, kBlock);
+      __syncthreads();
+    }
   }
   const int64_t n_items = p.B * p.tasks * p.n_seg_grid;
   for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {      // persistent workgroups
@@ -365,9 +367,10 @@ template <typename T> hipError_t launch_verify_tree(TreeParams p, hipStream_t s)
   int n_seg = int((p.V / E + 1 + kSegVecsTotal - 1) / kSegVecsTotal);
   if (n_seg > p.n_seg) n_seg = p.n_seg;
   p.n_seg_grid = (n_seg + kGroupSegs - 1) / kGroupSegs;
-  p.use_table = std::is_same<T, Bf16>::value && exp_table_usable(p.rT) ? 1 : 0;
+  // the binary16 table would leave one workgroup of 256 threads per compute unit: bf16 rows only
+  p.use_table = std::is_same<T, Bf16>::value && exp_table_usable<T>(p.rT) ? 1 : 0;
   const int64_t grid = std::min<int64_t>(p.B * p.tasks * p.n_seg_grid, sweep_grid_limit());
-  hipLaunchKernelGGL(tree_sweep_kernel<T>, dim3(unsigned(grid)), dim3(kBlock), p.use_table ? kTabBytes : 0, s, p);
+  hipLaunchKernelGGL(tree_sweep_kernel<T>, dim3(unsigned(grid)), dim3(kBlock), p.use_table ? ExpTab<T>::kBytes : 0, s, p);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(tree_finish_kernel<T>, dim3(unsigned(p.B * p.tasks)), dim3(kBlock), 0, s, p);
   if ((e = hipGetLastError()) != hipSuccess) return e;

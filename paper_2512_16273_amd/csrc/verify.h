@@ -136,9 +136,11 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
     if (lane == 0) { jstar_l = j0; flags_l = 0; }
   }
   double* table = nullptr;
-  if (std::is_same<T, Bf16>::value && p.use_table) {
-    table = reinterpret_cast<double*>(dyn_lds);
-    build_exp_table(table, p.rT, kResThreads);
+  if constexpr (ExpTab<T>::kHas) {
+    if (p.use_table) {
+      table = reinterpret_cast<double*>(dyn_lds);
+      build_exp_table<T>(table, p.rT, kResThreads);
+    }
   }
   __syncthreads();
   const int jstar = jstar_l;
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
       }
     };
     bool direct = true;
-    if constexpr (std::is_same<T, Bf16>::value) {
+    if constexpr (ExpTab<T>::kHas) {
       if (table != nullptr) {
         int flags = 0;
         uint4 d[kSegVecs], dn[kSegVecs];
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
           double acc = 0.0;
 #pragma unroll
           for (int i = 0; i < kSegVecs; ++i)
-            if (vbase + i * 64 < rs.nvec) acc += table_vec_sum(d[i], table, p.rT, flags);
+            if (vbase + i * 64 < rs.nvec) acc += table_vec_sum<T>(d[i], table, p.rT, flags);
           const double run_sum = wave_sum_f64(acc);
           if (lane == 0) subs_l[run] = run_sum;
           if (run + kResWaves < n_runs) {
@@ -332,8 +334,13 @@ template <typename T> hipError_t launch_verify(VerifyParams p, hipStream_t s, in
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (phases & 2) {
-    p.use_table = std::is_same<T, Bf16>::value && exp_table_usable(p.rT) ? 1 : 0;
-    hipLaunchKernelGGL(verify_resample_kernel<T>, dim3(unsigned(p.B)), dim3(kResThreads), p.use_table ? kTabBytes : 0, s, p);
+    p.use_table = exp_table_usable<T>(p.rT) ? 1 : 0;
+    const size_t lds = p.use_table ? ExpTab<T>::kBytes : 0;
+    if (lds > 48 * 1024 &&
+        (e = hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_resample_kernel<T>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, int(lds))) != hipSuccess)
+      return e;
+    hipLaunchKernelGGL(verify_resample_kernel<T>, dim3(unsigned(p.B)), dim3(kResThreads), lds, s, p);
     e = hipGetLastError();
   }
   return e;

@@ -52,7 +52,7 @@ def test_truncate_strided_rows(tslt):
 def test_truncate_degenerate_rows(tslt):
     V = 6000
     g = torch.Generator().manual_seed(1)
-    base = (torch.randn(12, V, generator=g) * 2).to(torch.bfloat16).float()
+    base = (torch.randn(13, V, generator=g) * 2).to(torch.bfloat16).float()
     rows = base.clone()
     rows[0] = 1.25                                            # all equal
     rows[1] = torch.where(torch.arange(V) % 3 == 0, 2.0, -1.0)  # two values
@@ -67,6 +67,7 @@ def test_truncate_degenerate_rows(tslt):
     rows[9, 1::2] = -0.0                                       # signed zeros are one value
     rows[10, :3000] = -float("inf")
     rows[11] = base[11].abs() * -50                            # huge spread
+    rows[12] = (torch.arange(V) % 3 - 1).float() * 3e-6        # 0 and +-3e-6: subnormal as binary16
     for dt in (torch.float32, torch.bfloat16, torch.float16):
         z = rows.to(dt).to(DEV)
         for (k, p, cap) in ((16, 0.0, 16), (0, 0.9, 256), (300, 0.0, 512)):

@@ -93,6 +93,34 @@ def test_verify_forced_paths_and_broken_rows(tslt):
     print(P.compare_verify(out, v, label="forced"), v["accept_len"], v["status"])
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_verify_rows_outside_the_exp_table(tslt, dtype):
+    """Target rows of 16-bit logits whose values leave the magnitude range that the resampling sweep tabulates:
+    tiny values, zeros and subnormals, large ones, and ones whose scaled value is beyond the range in which
+    terms may be referenced to 0."""
+    w = W.scaled(W.WORKLOADS["chain_topk"], B=6, V=9001, gamma=3, dtype=dtype)
+    chain = W.make_chain(w, 11, DEV)
+    target = chain["target"].float()
+    target[0] *= 1e-3                                  # everything below the table
+    target[1, :, ::3] = 0.0
+    target[1, :, 1::3] = -0.0
+    target[1, :, 2::9] = 3e-6 if dtype == "f16" else 1e-39     # subnormal in the storage type
+    target[2] *= 10.0                                  # much of the row above the table
+    target[3, :, ::7] = -500.0                         # |s| = 625 > 600
+    target[4, :, 5::11] = 490.0
+    chain["target"] = target.to(chain["target"].dtype)
+    u_acc = chain["u_accept"].clone()
+    u_acc[:, 0] = 0.99999994                           # reject at once wherever the ratio is below 1
+    chain["u_accept"] = u_acc
+    ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), w.T, w.top_k, w.top_p, w.k_cap,
+                         P.to_np(chain["u_sample"]), P.to_np(u_acc), P.to_np(chain["u_resample"]))
+    out = run_verify_from_oracle_inputs(tslt, w, chain, ref)
+    torch.cuda.synchronize()
+    v = ref["verify"]
+    assert np.all(v["status"] == 0)
+    print(dtype, P.compare_verify(out, v, label="table-edges"), v["accept_len"])
+
+
 def test_verify_argument_errors(tslt):
     w = W.scaled(W.WORKLOADS["chain_topk"], B=2, V=3000, gamma=2)
     chain = W.make_chain(w, 3, DEV)
