@@ -62,7 +62,8 @@ class ChainPlan:
                     ("verify_accept", "verify_accept_kernel", self.accept, B * G * V * s + sparse_r),
                     ("verify_resample", "verify_resample_kernel", self.resample, B * V * s)]
         self.total_bytes = B * G * V * s + B * (G + 1) * V * s + sparse_w + sparse_r
-        self.describe = (f"{w.name}: B={B} gamma={G} V={V} {w.dtype} logits, T={w.T}, top_k={w.top_k}, top_p={w.top_p}, "
+        self.describe = (f"{w.name}: B={B} gamma={G} V={V} {w.dtype} logits{f' shifted by {w.shift:+g}' if w.shift else ''}, "
+                         f"T={w.T}, top_k={w.top_k}, top_p={w.top_p}, "
                          f"k_cap={K}; {n_sets} rotating input sets; truncate_sample+verify per step")
 
     def _verify(self, c, phase):
@@ -190,6 +191,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--workload", default="large_vocab")
     ap.add_argument("--dtype", default="", choices=["", "f32", "bf16", "f16"], help="override the workload's logit storage type")
+    ap.add_argument("--shift", type=float, default=0.0, help="constant added to every logit of the workload (the Zipf recipe "
+                    "centres a row's bulk near -ln V; a shift of +ln V - 1 centres it on 0, where 16-bit formats are densest)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's B (sequences or trees)")
     ap.add_argument("--sets", type=int, default=0, help="independent input sets rotated between steps (default 3; 1 for tree)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -215,6 +218,8 @@ def main():
         w = W.scaled(w, B=args.batch)
     if args.dtype:
         w = W.scaled(w, dtype=args.dtype)
+    if args.shift != 0.0:
+        w = W.scaled(w, shift=args.shift)
     is_tree = len(w.expansion) > 0
     n_sets = args.sets if args.sets > 0 else (1 if is_tree else 3)
     plan = (TreePlan if is_tree else ChainPlan)(w, n_sets, torch, tslt, W, dev)

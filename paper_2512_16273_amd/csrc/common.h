@@ -29,6 +29,13 @@ template <> struct ElemTraits<F16> {
 __device__ __forceinline__ float as_f32(uint32_t b) { return __uint_as_float(b); }
 __device__ __forceinline__ uint32_t as_u32(float f) { return __float_as_uint(f); }
 
+// A pointer into device memory, typed as such.  Where the compiler cannot prove that a pointer is global
+// it emits flat loads; those also count against the LDS counter, so that every wait for an LDS access
+// waits for them too and a kernel that prefetches rows while it works in LDS loses the overlap.
+template <typename U> __device__ __forceinline__ const U __attribute__((address_space(1)))* as_global(const U* p) {
+  return (const U __attribute__((address_space(1)))*)p;
+}
+
 // Element i of a 16-byte vector, widened exactly to fp32.
 template <typename T> __device__ __forceinline__ void unpack(const uint4& w, float (&v)[ElemTraits<T>::kPerVec]);
 template <> __device__ __forceinline__ void unpack<float>(const uint4& w, float (&v)[4]) {
@@ -65,14 +72,14 @@ template <> __device__ __forceinline__ uint4 neg_inf_vec<F16>() {
 // Scalar load of element i of a row, any alignment of the element type.
 template <typename T> __device__ __forceinline__ float load_elem(const void* row, int64_t i);
 template <> __device__ __forceinline__ float load_elem<float>(const void* row, int64_t i) {
-  return reinterpret_cast<const float*>(row)[i];
+  return as_global(reinterpret_cast<const float*>(row))[i];
 }
 template <> __device__ __forceinline__ float load_elem<Bf16>(const void* row, int64_t i) {
-  return as_f32(uint32_t(reinterpret_cast<const uint16_t*>(row)[i]) << 16);
+  return as_f32(uint32_t(as_global(reinterpret_cast<const uint16_t*>(row))[i]) << 16);
 }
 
 template <> __device__ __forceinline__ float load_elem<F16>(const void* row, int64_t i) {
-  return f16_lo(reinterpret_cast<const uint16_t*>(row)[i]);
+  return f16_lo(as_global(reinterpret_cast<const uint16_t*>(row))[i]);
 }
 
 // Order-preserving map fp32 -> uint32 (larger value, larger key).  -0.0 must be folded into +0.0 by
@@ -98,11 +105,11 @@ __device__ __forceinline__ uint32_t cand_index(uint64_t c) { return 0xFFFFFFFFu 
 // 16-byte streaming load (read-once data: do not keep it in the caches longer than needed).
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_vec_stream(const uint4* p) {
-  u32x4_t r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  u32x4_t r = __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4_t*>(p)));
   return make_uint4(r.x, r.y, r.z, r.w);
 }
 __device__ __forceinline__ uint4 load_vec(const uint4* p) {
-  u32x4_t r = *reinterpret_cast<const u32x4_t*>(p);
+  u32x4_t r = *as_global(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(r.x, r.y, r.z, r.w);
 }
 

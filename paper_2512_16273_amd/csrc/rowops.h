@@ -45,7 +45,7 @@ struct VerifyShared {
 
 // A table of exp(s), s = fl32(z / T), for every 16-bit logit z of a magnitude range that holds the bulk of
 // a row: the fp64 sums over the row then cost one LDS read per element instead of an fp64 exponential.
-//   bfloat16  2^-6 <= |z| < 2^7   3328 values, 26 KB
+//   bfloat16  2^-14 <= |z| < 2^7   5376 values, 42 KB  (logits centred on 0 have many small values)
 //   binary16  2^-2 <= |z| < 2^5  14336 values, 112 KB
 // With the 16 bits of an element rotated left by one (sign in bit 0), entry 1 + (rotated - 2*kLo) holds
 // its value; entries 0 and kEntries + 1 hold NaN and stand for everything below and above the table's
@@ -55,16 +55,18 @@ struct VerifyShared {
 constexpr float kTabMaxS = 600.0f;
 template <typename T> struct ExpTab {
   static constexpr bool kHas = false;
+  static constexpr bool kSampled = false;
   static constexpr size_t kBytes = 0;
 };
 template <> struct ExpTab<Bf16> {
   static constexpr bool kHas = true;
-  static constexpr int kLo = (127 - 6) << 7;       // bits of the smallest magnitude covered
-  static constexpr int kSpan = 13 << 7;            // magnitudes covered
+  static constexpr int kLo = (127 - 14) << 7;      // bits of the smallest magnitude covered
+  static constexpr int kSpan = 21 << 7;            // magnitudes covered
   static constexpr int kEntries = 2 * kSpan;
   static constexpr size_t kBytes = size_t(kEntries + 2) * sizeof(double);
   static constexpr float kMaxAbs = 128.0f;
   static constexpr uint32_t kInf = 0x7F80u;
+  static constexpr bool kSampled = false;          // the range is wide enough for any plausible row
   static __device__ __forceinline__ float widen(uint32_t bits) { return __uint_as_float(bits << 16); }
 };
 template <> struct ExpTab<F16> {
@@ -75,6 +77,7 @@ template <> struct ExpTab<F16> {
   static constexpr size_t kBytes = size_t(kEntries + 2) * sizeof(double);
   static constexpr float kMaxAbs = 32.0f;
   static constexpr uint32_t kInf = 0x7C00u;
+  static constexpr bool kSampled = true;           // a row whose bulk lies near 0 is mostly below the range
   static __device__ __forceinline__ float widen(uint32_t bits) { return f16_lo(bits); }
 };
 template <typename T> inline bool exp_table_usable(float rT) {
@@ -101,18 +104,6 @@ template <typename T> __device__ __forceinline__ double exp_table_entry(int i, f
 // Fills the table with all `threads` threads of the workgroup; the caller synchronises.
 template <typename T> __device__ __forceinline__ void build_exp_table(double* table, float rT, int threads) {
   for (int i = threadIdx.x; i < ExpTab<T>::kEntries + 2; i += threads) table[i] = exp_table_entry<T>(i, rT);
-}
-
-// exp(s) of one 16-bit element given by its bits, for the elements the table does not cover; -1 for
-// NaN or +inf, -2 for a value that needs the maximum-referenced path
-template <typename T> __device__ __noinline__ double exp_term_16(uint32_t b, float rT) {
-  using TB = ExpTab<T>;
-  const uint32_t m = b & 0x7FFFu;
-  if (m > TB::kInf || b == TB::kInf) return -1.0;
-  if (b == (0x8000u | TB::kInf)) return 0.0;                        // -inf: probability 0
-  const float s = __fmul_rn(TB::widen(b), rT);
-  if (fabsf(s) > kTabMaxS) return -2.0;
-  return exp64(double(s));
 }
 
 // Sum of exp(s) over the 8 elements of a 16-bit vector through the table.  The index arithmetic runs on
@@ -146,18 +137,18 @@ __device__ __forceinline__ double table_vec_sum(const uint4& d, const double* ta
   }
   double s = s0 + s1;
   if (s != s) {
+    // every element of this lane's vector directly; branch-free, so that a wave in which some lane comes
+    // here for every vector (a row with many values outside the table) runs at the pace of the direct
+    // path and not at that of a divergent loop.  flags: 1 = NaN or +inf, 2 = |s| beyond kTabMaxS
     s = 0.0;
-#pragma unroll 1
+#pragma unroll
     for (int e = 0; e < 8; ++e) {
       const uint32_t b = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-      const uint32_t r = (b & 0x7FFFu) - uint32_t(TB::kLo);
-      double t = 0.0;
-      if (r < uint32_t(TB::kSpan)) t = table[1 + r * 2 + (b >> 15)];
-      else {
-        t = exp_term_16<T>(b, rT);
-        if (t < 0.0) { flags |= int(-t); t = 0.0; }
-      }
-      s += t;
+      const float sv = __fmul_rn(TB::widen(b), rT);
+      const bool neg_inf = b == (0x8000u | TB::kInf);
+      flags |= ((b & 0x7FFFu) > TB::kInf || b == TB::kInf) ? 1 : 0;
+      flags |= (!neg_inf && fabsf(sv) > kTabMaxS) ? 2 : 0;
+      s += exp64(double(sv));                                       // -inf gives exactly 0
     }
   }
   return s;
@@ -182,7 +173,7 @@ template <typename T>
 __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit& rs, int64_t V, float rT, float k2,
                                                 const int32_t* qi, const float* ql, int count, VerifyShared& sh,
                                                 double (&p_s)[kSetPer], double (&q_s)[kSetPer], int (&yi)[kSetPer],
-                                                double& p_out, bool& ok, int& st) {
+                                                double& p_out, bool& ok, int& st, int* table_miss = nullptr) {
   constexpr int E = ElemTraits<T>::kPerVec;
   const int tid = threadIdx.x;
   const int n_edge = rs.head + rs.tail;
@@ -245,6 +236,23 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
       }
       dacc += double((acc0 + acc1) + (acc2 + acc3));
     };
+    if constexpr (ExpTab<T>::kSampled) {
+      // how many values of the first batch lie outside the exp table's range (a hint for the sweep that
+      // may follow; this thread's share, the caller adds them up)
+      if (table_miss != nullptr && n_full > 0) {
+        int miss = 0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const uint32_t w[4] = {pipe[0][u].x, pipe[0][u].y, pipe[0][u].z, pipe[0][u].w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const uint32_t m = ((w[e >> 1] >> ((e & 1) * 16)) & 0x7FFFu) - uint32_t(ExpTab<T>::kLo);
+            miss += m >= uint32_t(ExpTab<T>::kSpan) ? 1 : 0;
+          }
+        }
+        *table_miss = miss;
+      }
+    }
     for (uint32_t b = 0; b < n_full; b += kAccDepth) {
 #pragma unroll
       for (int s = 0; s < kAccDepth; ++s) {

@@ -47,6 +47,9 @@ inline void verify_carve_workspace(VerifyParams& p, void* ws) {
   p.row_status = reinterpret_cast<int32_t*>(w);
 }
 
+// row_status bit for kernel B only: a sample of the row lies largely outside the exp table's range
+constexpr int kRowTablePoor = 1 << 20;
+
 template <typename T> __device__ __forceinline__ const void* target_row(const VerifyParams& p, int64_t b, int j) {
   return reinterpret_cast<const char*>(p.target) +
          (size_t(b) * (p.gamma + 1) + j) * size_t(p.row_stride) * ElemTraits<T>::kBytes;
@@ -69,12 +72,19 @@ __global__ __launch_bounds__(kBlock) void verify_accept_kernel(const VerifyParam
   double p_s[kSetPer], q_s[kSetPer], p_out;
   int yi[kSetPer], st;
   bool ok;
+  // A format whose exp table covers a part of its range only: the first batch of the row (4 * kBlock
+  // vectors) says whether kernel B should use the table on this row.  A wave pays for one value outside
+  // the table as if its whole vector were outside, so the table loses to the direct path once about 1
+  // value in 500 is outside.
+  int miss = 0;
   eval_row_on_set<T>(row, rs, p.V, p.rT, p.k2, p.q_idx + size_t(r) * p.k_cap, p.q_logit + size_t(r) * p.k_cap, count, sh,
-                     p_s, q_s, yi, p_out, ok, st);
+                     p_s, q_s, yi, p_out, ok, st, &miss);
+  if constexpr (ExpTab<T>::kSampled) miss = wave_sum_i32(miss);
   const int x = p.draft_tokens[r];
   double beta = 0.0;
-  if (tid == 0) { sh.bcast_d[0] = -1.0; sh.bcast_i[0] = 0; }
+  if (tid == 0) { sh.bcast_d[0] = -1.0; sh.bcast_i[0] = 0; sh.bcast_i[1] = 0; }
   __syncthreads();
+  if (ExpTab<T>::kSampled && miss && lane_id() == 0) atomicAdd(&sh.bcast_i[1], miss);
 #pragma unroll
   for (int k = 0; k < kSetPer; ++k) {
     if (tid + k * kBlock < count && ok) {
@@ -98,6 +108,7 @@ __global__ __launch_bounds__(kBlock) void verify_accept_kernel(const VerifyParam
       }
     }
     p.flags[r] = flag;
+    if (ExpTab<T>::kSampled && sh.bcast_i[1] * 500 >= 4 * 8 * kBlock) st |= kRowTablePoor;
     p.row_status[r] = st;
     if (p.out_ratio) p.out_ratio[r] = ok ? float(ratio) : NAN;
     if (p.out_beta) p.out_beta[r] = ok ? float(beta) : NAN;
@@ -120,7 +131,7 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
   __shared__ double subs_l[kMaxSegs * kSubChunks];     // mass of every run, in its segment's units
   __shared__ SegResult segs_l[kMaxSegs + 2];
   __shared__ float run_max[kResWaves];
-  __shared__ int jstar_l, flags_l;
+  __shared__ int jstar_l, flags_l, miss_l;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -133,11 +144,22 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
     for (int j = lane; j < p.gamma; j += 64)
       if (p.flags[b * p.gamma + j] != 1) { j0 = j; break; }
     j0 = -wave_max_i32(-j0);        // the smallest over the wave
-    if (lane == 0) { jstar_l = j0; flags_l = 0; }
+    if (lane == 0) {
+      jstar_l = j0; flags_l = 0;
+      miss_l = (ExpTab<T>::kSampled && j0 < p.gamma) ? (p.row_status[b * p.gamma + j0] & kRowTablePoor) : 0;
+    }
   }
   double* table = nullptr;
   if constexpr (ExpTab<T>::kHas) {
-    if (p.use_table) {
+    bool by_table = p.use_table != 0;
+    if constexpr (ExpTab<T>::kSampled) {
+      // kernel A has looked at a sample of the row (the bonus row it has not seen: the table is tried)
+      if (by_table) {
+        __syncthreads();
+        by_table = miss_l == 0;
+      }
+    }
+    if (by_table) {
       table = reinterpret_cast<double*>(dyn_lds);
       build_exp_table<T>(table, p.rT, kResThreads);
     }
@@ -158,7 +180,7 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
   float u_res = 0.0f;
   SetEntries se;
   if (wave < kWaves) {
-    for (int j = tid; j <= jstar && j < p.gamma; j += kBlock) st |= p.row_status[b * p.gamma + j];
+    for (int j = tid; j <= jstar && j < p.gamma; j += kBlock) st |= p.row_status[b * p.gamma + j] & ~kRowTablePoor;
     u_res = p.u_resample[b * (p.gamma + 1) + jstar];
     count = residual ? p.q_count[r] : 0;
     count = count < 0 ? 0 : (count > p.k_cap ? p.k_cap : count);

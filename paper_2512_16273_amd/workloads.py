@@ -12,7 +12,7 @@ carries most of the mass, which is the property Section 5.1 relies on).
 
 Recipe (every config):
   * one torch.Generator per call, seeded with (seed, config id);
-  * base row (fp32) = N(0, sigma^2) + bias; bias is either
+  * base row (fp32) = N(0, sigma^2) + bias (+ `shift`, 0 in every benchmark configuration); bias is either
       - `boost`: n distinct random indices per row get +amount, or
       - `zipf`:  -a * ln(rank + 1), rank 0-based through a random permutation
                  drawn per row;
@@ -48,6 +48,7 @@ class Workload:
     boost: Tuple[int, float] = (0, 0.0)   # (n indices, amount)
     expansion: Tuple[int, ...] = ()       # tree: k_1..k_L
     without_replacement: bool = False     # tree: how candidates are drawn
+    shift: float = 0.0                    # added to every logit (a softmax does not see it; the number format does)
     config_id: int = 0
 
 
@@ -99,6 +100,8 @@ def _base_rows(w: Workload, n_rows: int, g: torch.Generator, device) -> torch.Te
         keys = torch.rand(n_rows, V, generator=g, device=device, dtype=torch.float32)
         hot = torch.topk(keys, n_boost, dim=1).indices            # n distinct indices per row
         base.scatter_add_(1, hot, torch.full_like(hot, amount, dtype=torch.float32))
+    if w.shift != 0.0:
+        base += w.shift
     return base
 
 
