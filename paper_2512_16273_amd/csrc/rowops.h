@@ -183,14 +183,21 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
   constexpr int U = 4;
   const uint32_t n_full = uint32_t(rs.nvec / (U * kBlock));      // batches of U complete tiles
   uint4 pipe[kAccDepth][U];
+  // Every request of the pipeline is unconditional: a vector past the row's end is read from the row's
+  // last vector instead and never used.  With conditional requests the number of loads in flight is not
+  // known where a wait is placed, and each wait for one batch waits for all of them.
+  const uint32_t last_vec = rs.nvec > 0 ? uint32_t(rs.nvec - 1) : 0u;
   auto issue = [&](uint32_t b, uint4 (&q)[U]) {
-    const uint4* src = rs.body + size_t(b) * (U * kBlock) + tid;
 #pragma unroll
-    for (int u = 0; u < U; ++u) q[u] = load_vec_stream(src + u * kBlock);
+    for (int u = 0; u < U; ++u) {
+      const uint32_t vi = b * (U * kBlock) + u * kBlock + tid;
+      q[u] = load_vec_stream(rs.body + (vi < last_vec ? vi : last_vec));
+    }
   };
+  if (n_full > 0) {
 #pragma unroll
-  for (int s = 0; s < kAccDepth; ++s)
-    if (uint32_t(s) < n_full) issue(uint32_t(s), pipe[s]);
+    for (int s = 0; s < kAccDepth; ++s) issue(uint32_t(s), pipe[s]);
+  }
 
   float tv[kSetPer];       // raw target logit at entry
   float gmax = -INFINITY;
@@ -256,10 +263,8 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
     for (uint32_t b = 0; b < n_full; b += kAccDepth) {
 #pragma unroll
       for (int s = 0; s < kAccDepth; ++s) {
-        if (b + s < n_full) {
-          consume(pipe[s]);
-          if (b + s + kAccDepth < n_full) issue(b + s + kAccDepth, pipe[s]);
-        }
+        if (b + s < n_full) consume(pipe[s]);
+        issue(b + s + kAccDepth, pipe[s]);
       }
     }
     for (int64_t t0 = int64_t(n_full) * U; t0 < n_tiles; t0 += U) {      // the ragged end

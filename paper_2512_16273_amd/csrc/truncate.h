@@ -370,21 +370,22 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
   const int64_t row_i = blockIdx.x;
   // The sample: the first tile of kBatch batches at equal distances; a row with fewer than 4*kBatch
   // complete batches uses its first kBatch tiles.
+  // (Every load of the pass below is unconditional: an address past the row's end is replaced by that of
+  // the row's last vector and the value by -inf afterwards.  With conditional loads the number of loads in
+  // flight is not known where a wait is placed, and a wait for one batch waits for all that were
+  // requested after it as well.)
   auto load_sample = [&](const RowSplit& r, uint4 (&q)[kBatch]) {
-    const uint32_t nv = uint32_t(r.nvec);
+    const uint32_t nv = uint32_t(r.nvec);            // > 0 here
     const uint32_t nf = nv / (kBatch * NT);
-    if (nf >= 4) {
-      const uint32_t stride = (nf / 4) * kBatch;
+    const uint32_t stride = nf >= 4 ? (nf / 4) * kBatch : 1;
 #pragma unroll
-      for (int u = 0; u < kBatch; ++u) q[u] = load_vec_stream(&r.body[u * stride * NT + tid]);
-    } else {
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const uint32_t vi = u * NT + tid;
-        q[u] = neg_inf_vec<T>();
-        if (vi < nv) q[u] = load_vec_stream(&r.body[vi]);
-      }
+    for (int u = 0; u < kBatch; ++u) {
+      const uint32_t vi = u * stride * NT + tid;
+      q[u] = load_vec_stream(&r.body[vi < nv ? vi : nv - 1]);
     }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u)
+      if (u * stride * NT + tid >= nv) q[u] = neg_inf_vec<T>();
   };
   const void* row = reinterpret_cast<const char*>(p.logits) + size_t(row_i) * size_t(p.row_stride) * ElemTraits<T>::kBytes;
   const RowSplit rs = split_row<T>(row, p.V);
@@ -413,27 +414,22 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
     const uint32_t n_pipe = long_row ? n_full + (n_tiles > n_full * kBatch ? 1u : 0u) : 0u;
     uint32_t skip_b = 0, skips_left = kBatch;
     const uint32_t stride_b = s_stride / kBatch;
+    const uint32_t last_vec = nvec - 1;
     auto issue = [&](uint32_t b, uint4 (&q)[kBatch]) {
       const uint32_t v0 = b * (kBatch * NT) + tid;
-      if (b < n_full) {
-        const uint4* src = rs.body + v0;
-        const bool skip = skips_left > 0 && b == skip_b;
-        if (skip) { skip_b += stride_b; --skips_left; }
-        q[0] = neg_inf_vec<T>();
-        if (!skip) q[0] = load_vec_stream(src);
+      // the first tile of a sample batch is in registers already: its slot repeats the second tile's load
+      const bool skip = skips_left > 0 && b == skip_b;
+      if (skip) { skip_b += stride_b; --skips_left; }
 #pragma unroll
-        for (int u = 1; u < kBatch; ++u) q[u] = load_vec_stream(src + u * NT);
-      } else {
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-          q[u] = neg_inf_vec<T>();
-          if (v0 + u * NT < nvec) q[u] = load_vec_stream(&rs.body[v0 + u * NT]);
-        }
+      for (int u = 0; u < kBatch; ++u) {
+        const uint32_t vi = v0 + ((u == 0 && skip) ? 1 : u) * NT;
+        q[u] = load_vec_stream(&rs.body[vi < last_vec ? vi : last_vec]);
       }
     };
+    if (n_pipe > 0) {
 #pragma unroll
-    for (int s = 0; s < kDepth; ++s)
-      if (uint32_t(s) < n_pipe) issue(uint32_t(s), pipe[s]);
+      for (int s = 0; s < kDepth; ++s) issue(uint32_t(s), pipe[s]);
+    }
     float tmax = -INFINITY;
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
@@ -534,17 +530,27 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
       uint32_t first_generic_tile = kBatch;             // short rows: everything after the sample tiles
       if (long_row) {
         // complete batches
+        uint32_t seen_b = 0, seen_left = kBatch;
         for (uint32_t b = 0; b < n_pipe; b += kDepth) {
 #pragma unroll
           for (int s = 0; s < kDepth; ++s) {
             const uint32_t bb = b + s;
-            if (bb < n_pipe) {
+            if (bb < n_pipe) {                                      // wave-uniform, no loads inside
               const uint32_t v0 = bb * (kBatch * NT) + tid;
+              if (seen_left > 0 && bb == seen_b) {                  // a sample batch: its first tile is done
+                seen_b += stride_b; --seen_left;
+                pipe[s][0] = neg_inf_vec<T>();
+              }
+              if (bb >= n_full) {                                   // the ragged end
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u)
+                  if (v0 + u * NT >= nvec) pipe[s][u] = neg_inf_vec<T>();
+              }
               process_pair(pipe[s][0], pipe[s][1], v0, v0 + NT);
               process_pair(pipe[s][2], pipe[s][3], v0 + 2 * NT, v0 + 3 * NT);
               flush();
-              if (bb + kDepth < n_pipe) issue(bb + kDepth, pipe[s]);
             }
+            issue(bb + kDepth, pipe[s]);
           }
         }
         first_generic_tile = n_tiles;
