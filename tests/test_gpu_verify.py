@@ -32,6 +32,10 @@ def run_verify_from_oracle_inputs(tslt, w, chain, ref):
     ("f16-topk", "chain_topk", dict(B=12, V=20011, dtype="f16")),
     ("f16-topp", "chain_topp", dict(B=10, dtype="f16")),
     ("f16-k1024", "stress", dict(B=3, gamma=4, V=70000, dtype="f16")),
+    # the bulk of a row moved to 0, where the 16-bit formats have most of their small values: bf16 rows stay
+    # inside the exp table, binary16 rows leave it and are swept without it
+    ("bf16-centred", "chain_topp", dict(B=8, shift=9.4)),
+    ("f16-centred", "chain_topp", dict(B=8, dtype="f16", shift=9.4)),
 ])
 def test_verify_matches_oracle(tslt, name, base, kw):
     w = W.scaled(W.WORKLOADS[base], **kw)
