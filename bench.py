@@ -42,6 +42,7 @@ class ChainPlan:
         self.w, self.torch, self.tslt = w, torch, tslt
         B, G, V, K = w.B, w.gamma, w.V, w.k_cap
         self.sets = [W.make_chain(w, 100 + i, dev) for i in range(n_sets)]
+        self.first_stage = 0
         i32, f32 = torch.int32, torch.float32
         # preallocated outputs and workspace: nothing is allocated inside the timed region
         self.tr = {"idx": torch.empty(B * G, K, dtype=i32, device=dev), "logit": torch.empty(B * G, K, dtype=f32, device=dev),
@@ -70,7 +71,8 @@ class ChainPlan:
         w, t = self.w, self.tr
         B, G, K = w.B, w.gamma, w.k_cap
         self.tslt.verify(c["target"], w.T, t["idx"].view(B, G, K), t["logit"].view(B, G, K), t["count"].view(B, G),
-                         t["token"].view(B, G), c["u_accept"], c["u_resample"], out=self.vf, workspace=self.ws, phase=phase)
+                         t["token"].view(B, G), c["u_accept"], c["u_resample"], out=self.vf, workspace=self.ws, phase=phase,
+                         first_stage=self.first_stage)
 
     def truncate(self, c):
         w = self.w
@@ -193,6 +195,9 @@ def main():
     ap.add_argument("--dtype", default="", choices=["", "f32", "bf16", "f16"], help="override the workload's logit storage type")
     ap.add_argument("--shift", type=float, default=0.0, help="constant added to every logit of the workload (the Zipf recipe "
                     "centres a row's bulk near -ln V; a shift of +ln V - 1 centres it on 0, where 16-bit formats are densest)")
+    ap.add_argument("--first-stage", type=int, default=0, help="chain workloads: take the acceptance tests in stages "
+                    "(tslt_verify_accept_staged) with this many positions in the first stage; 0 = one launch")
+    ap.add_argument("--no-staged", action="store_true", help="skip the extra measurement with staged acceptance tests")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's B (sequences or trees)")
     ap.add_argument("--sets", type=int, default=0, help="independent input sets rotated between steps (default 3; 1 for tree)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -223,6 +228,9 @@ def main():
     is_tree = len(w.expansion) > 0
     n_sets = args.sets if args.sets > 0 else (1 if is_tree else 3)
     plan = (TreePlan if is_tree else ChainPlan)(w, n_sets, torch, tslt, W, dev)
+    if args.first_stage > 0 and not is_tree:
+        plan.first_stage = args.first_stage
+        plan.describe += f"; acceptance in stages from {args.first_stage} positions"
     sets, ops = plan.sets, plan.ops
     n_ops = len(ops)
 
@@ -290,6 +298,25 @@ def main():
         "hbm_frac_whole_step": round(plan.total_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
         "kernels_untimed_pass": kernels, "roofline": roofline,
     }
+    if not is_tree and plan.first_stage > 0:
+        # rows after a rejection are not read: the all-rows byte count does not describe this run
+        res["hbm_GBps_whole_step"] = res["hbm_frac_whole_step"] = None
+    elif not is_tree and not args.no_staged:
+        # beside the headline (every position evaluated): the same steps with the acceptance tests taken in
+        # two stages, which does not read the target rows behind a rejection found in the first half
+        plan.first_stage = max(1, w.gamma // 2)
+        for i in range(3):
+            step(sets[i % len(sets)])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for i in range(args.steps):
+            step(sets[i % len(sets)])
+        torch.cuda.synchronize()
+        dt1 = time.perf_counter() - t1
+        plan.first_stage = 0
+        res["staged_acceptance"] = {"first_stage": max(1, w.gamma // 2), "ms_per_step": round(dt1 / args.steps * 1e3, 4),
+                                    "value": round(plan.positions * args.steps / dt1, 1), "unit": "draft positions/s",
+                                    "note": "same outputs (accept_len, tokens); ratio and beta of skipped positions are NaN"}
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)

@@ -217,6 +217,30 @@ int tslt_verify_resample(const void* target_logits, tslt_dtype dt, int64_t B, in
                          int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta,
                          int32_t* status, void* ws, size_t ws_bytes, void* stream);
 
+/* tslt_verify with the acceptance tests taken in stages (Algorithm 3 stops at the first rejection: the
+ * positions after it need not be looked at).  Stage 0 covers the first `first_stage` positions of every
+ * sequence, stage 1 the next `first_stage`, and every later stage twice as many as the one before it; a
+ * stage is one launch, and a sequence that an earlier stage has rejected is skipped in it, so the target
+ * rows of its remaining positions are never read.  accept_len, tokens and status are those of
+ * tslt_verify; out_ratio and out_beta are NaN at the positions of skipped stages (positions of the stage
+ * that holds the first rejection are all evaluated).  first_stage = 0 or >= gamma is tslt_verify itself.
+ * Pays when B * first_stage rows fill the GPU (B in the thousands); at a few hundred sequences the
+ * stages are too small to reach the memory bandwidth and the single launch is faster.
+ * tslt_verify_accept_staged is the staged counterpart of tslt_verify_accept; it is followed by
+ * tslt_verify_resample. */
+int tslt_verify_staged(const void* target_logits, tslt_dtype dt, int64_t B, int32_t gamma, int64_t V,
+                       int64_t row_stride, float target_temperature,
+                       const int32_t* q_idx, const float* q_logit, const int32_t* q_count, int32_t k_cap,
+                       const int32_t* draft_tokens, const float* u_accept, const float* u_resample,
+                       int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta,
+                       int32_t* status, void* ws, size_t ws_bytes, void* stream, int32_t first_stage);
+int tslt_verify_accept_staged(const void* target_logits, tslt_dtype dt, int64_t B, int32_t gamma, int64_t V,
+                              int64_t row_stride, float target_temperature,
+                              const int32_t* q_idx, const float* q_logit, const int32_t* q_count, int32_t k_cap,
+                              const int32_t* draft_tokens, const float* u_accept, const float* u_resample,
+                              int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta,
+                              int32_t* status, void* ws, size_t ws_bytes, void* stream, int32_t first_stage);
+
 /* Token-tree verification (Algorithm 8 with Algorithm 5 at every non-leaf node) for B trees.
  *
  * Nodes are stored breadth-first (Section 4.1): layer l has W_l = k_1*...*k_l nodes, the i-th node of

@@ -241,7 +241,7 @@ int tslt_sample(const int32_t* idx, const float* logit, const int32_t* count, in
   return TSLT_OK;
 }
 
-static int verify_impl(int phases, const char* name, const void* target_logits, tslt_dtype dt, int64_t B,
+static int verify_impl(int phases, int stage0, const char* name, const void* target_logits, tslt_dtype dt, int64_t B,
                        int32_t gamma, int64_t V, int64_t row_stride, float target_temperature, const int32_t* q_idx,
                        const float* q_logit, const int32_t* q_count, int32_t k_cap, const int32_t* draft_tokens,
                        const float* u_accept, const float* u_resample, int32_t* out_accept_len, int32_t* out_tokens,
@@ -250,6 +250,7 @@ static int verify_impl(int phases, const char* name, const void* target_logits, 
   if (B < 0 || gamma < 1 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "%s: bad shape", name);
   if (V > 0x7FFFFFFF || B * (int64_t(gamma) + 1) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: sizes must fit 31 bits", name);
   if (gamma > 4096) return fail(TSLT_ERR_UNSUPPORTED, "%s: gamma > 4096", name);
+  if (stage0 < 0) return fail(TSLT_ERR_INVALID_ARG, "%s: first_stage must be >= 0", name);
   if (tslt::row_segments(V) + 2 > tslt::kBlock) return fail(TSLT_ERR_UNSUPPORTED, "%s: V too large", name);
   if (B * int64_t(tslt::row_segments(V)) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: B too large", name);
   if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "%s: temperature must be > 0", name);
@@ -271,6 +272,7 @@ static int verify_impl(int phases, const char* name, const void* target_logits, 
   p.draft_tokens = draft_tokens; p.u_accept = u_accept; p.u_resample = u_resample;
   p.out_accept_len = out_accept_len; p.out_tokens = out_tokens; p.out_ratio = out_ratio; p.out_beta = out_beta;
   p.status = status;
+  p.stage0 = stage0 >= gamma ? 0 : stage0;
   tslt::verify_carve_workspace(p, ws);
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   hipError_t e = dt == TSLT_BF16 ? tslt::launch_verify<tslt::Bf16>(p, s, phases)
@@ -288,9 +290,15 @@ static int verify_impl(int phases, const char* name, const void* target_logits, 
   target_logits, dt, B, gamma, V, row_stride, target_temperature, q_idx, q_logit, q_count, k_cap, draft_tokens,   \
       u_accept, u_resample, out_accept_len, out_tokens, out_ratio, out_beta, status, ws, ws_bytes, stream
 
-int tslt_verify(TSLT_VERIFY_ARGS) { return verify_impl(3, "tslt_verify", TSLT_VERIFY_PASS); }
-int tslt_verify_accept(TSLT_VERIFY_ARGS) { return verify_impl(1, "tslt_verify_accept", TSLT_VERIFY_PASS); }
-int tslt_verify_resample(TSLT_VERIFY_ARGS) { return verify_impl(2, "tslt_verify_resample", TSLT_VERIFY_PASS); }
+int tslt_verify(TSLT_VERIFY_ARGS) { return verify_impl(3, 0, "tslt_verify", TSLT_VERIFY_PASS); }
+int tslt_verify_accept(TSLT_VERIFY_ARGS) { return verify_impl(1, 0, "tslt_verify_accept", TSLT_VERIFY_PASS); }
+int tslt_verify_resample(TSLT_VERIFY_ARGS) { return verify_impl(2, 0, "tslt_verify_resample", TSLT_VERIFY_PASS); }
+int tslt_verify_staged(TSLT_VERIFY_ARGS, int32_t first_stage) {
+  return verify_impl(3, first_stage, "tslt_verify_staged", TSLT_VERIFY_PASS);
+}
+int tslt_verify_accept_staged(TSLT_VERIFY_ARGS, int32_t first_stage) {
+  return verify_impl(1, first_stage, "tslt_verify_accept_staged", TSLT_VERIFY_PASS);
+}
 
 int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_t V, int64_t row_stride,
                      float target_temperature, int32_t depth, const int32_t* expansion, const int32_t* q_idx,

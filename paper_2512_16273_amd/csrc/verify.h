@@ -32,10 +32,13 @@ struct VerifyParams {
   float* out_beta;
   int32_t* status;
   // workspace
-  int32_t* flags;        // [B, gamma] 1 accepted, 0 rejected, 2 row unusable
+  int32_t* flags;        // [B, gamma] 1 accepted, 0 rejected, 2 row unusable, 3 not examined (staged mode)
   int32_t* row_status;   // [B, gamma]
   int use_table;         // kernel B sums bf16 rows through the exp table
+  int stage0;            // staged mode: positions in the first stage (0 = all positions in one launch)
+  int j_begin, j_count;  // the positions one launch of kernel A covers
 };
+constexpr int kFlagSkipped = 3;
 
 inline size_t verify_workspace_bytes(int64_t B, int64_t gamma, int64_t V, int k_cap) {
   (void)V; (void)k_cap;
@@ -62,9 +65,23 @@ template <typename T>
 __global__ __launch_bounds__(kBlock) void verify_accept_kernel(const VerifyParams p) {
   __shared__ VerifyShared sh;
   const int tid = threadIdx.x;
-  const int64_t r = blockIdx.x;            // row index in [0, B*gamma)
-  const int64_t b = r / p.gamma;
-  const int j = int(r - b * p.gamma);
+  const int64_t b = blockIdx.x / p.j_count;
+  const int j = p.j_begin + int(blockIdx.x - b * p.j_count);
+  const int64_t r = b * p.gamma + j;       // row index in [0, B*gamma)
+  if (p.j_begin > 0) {
+    // a later stage: nothing to do for a sequence that an earlier stage has rejected
+    int dead = 0;
+    for (int i = tid; i < p.j_begin; i += kBlock) dead |= p.flags[b * p.gamma + i] != 1 ? 1 : 0;
+    if (__syncthreads_or(dead)) {
+      if (tid == 0) {
+        p.flags[r] = kFlagSkipped;
+        p.row_status[r] = 0;
+        if (p.out_ratio) p.out_ratio[r] = NAN;
+        if (p.out_beta) p.out_beta[r] = NAN;
+      }
+      return;
+    }
+  }
   const void* row = target_row<T>(p, b, j);
   const RowSplit rs = split_row<T>(row, p.V);
   int count = p.q_count[r];
@@ -352,8 +369,16 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
 template <typename T> hipError_t launch_verify(VerifyParams p, hipStream_t s, int phases) {
   hipError_t e = hipSuccess;
   if (phases & 1) {
-    hipLaunchKernelGGL(verify_accept_kernel<T>, dim3(unsigned(p.B * p.gamma)), dim3(kBlock), 0, s, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    // stages of stage0, stage0, 2 * stage0, 4 * stage0, ... positions; one stage if stage0 is 0
+    int len = p.stage0 > 0 ? p.stage0 : p.gamma;
+    for (int j0 = 0, k = 0; j0 < p.gamma; ++k) {
+      p.j_begin = j0;
+      p.j_count = p.gamma - j0 < len ? p.gamma - j0 : len;
+      hipLaunchKernelGGL(verify_accept_kernel<T>, dim3(unsigned(p.B * p.j_count)), dim3(kBlock), 0, s, p);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+      j0 += p.j_count;
+      if (k > 0) len *= 2;
+    }
   }
   if (phases & 2) {
     p.use_table = exp_table_usable<T>(p.rT) ? 1 : 0;

@@ -24,7 +24,8 @@ PAYLOAD = {"f32": 0, "bf16": 1, "f16": 2}       # tslt_dtype codes of the format
 
 EXPORTS = ("tslt_version", "tslt_last_error", "tslt_workspace_bytes", "tslt_truncate", "tslt_truncate_sample", "tslt_sample",
            "tslt_pack_bound_words", "tslt_pack", "tslt_unpack",
-           "tslt_verify", "tslt_verify_accept", "tslt_verify_resample", "tslt_verify_tree")
+           "tslt_verify", "tslt_verify_accept", "tslt_verify_resample", "tslt_verify_staged", "tslt_verify_accept_staged",
+           "tslt_verify_tree")
 
 _lib = None
 
@@ -67,6 +68,9 @@ def load(path: Optional[str] = None):
     for fn in (lib.tslt_verify, lib.tslt_verify_accept, lib.tslt_verify_resample):
         fn.restype = c.c_int
         fn.argtypes = [vp, c.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    for fn in (lib.tslt_verify_staged, lib.tslt_verify_accept_staged):
+        fn.restype = c.c_int
+        fn.argtypes = [vp, c.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, i32]
     lib.tslt_verify_tree.restype = c.c_int
     lib.tslt_verify_tree.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, c.POINTER(i32), vp, vp, vp, i32, vp, vp,
                                      vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -214,12 +218,18 @@ def sample(idx: torch.Tensor, logit: torch.Tensor, count: torch.Tensor, u: torch
 
 def verify(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logit: torch.Tensor,
            q_count: torch.Tensor, draft_tokens: torch.Tensor, u_accept: torch.Tensor, u_resample: torch.Tensor,
-           out: Optional[dict] = None, workspace: Optional[torch.Tensor] = None, phase: str = "both") -> dict:
+           out: Optional[dict] = None, workspace: Optional[torch.Tensor] = None, phase: str = "both",
+           first_stage: int = 0) -> dict:
     """tslt_verify: target [B, gamma+1, V]; sparse sets [B, gamma, k_cap]; returns accept_len [B],
     tokens [B, gamma+1], ratio, beta [B, gamma], status [B].  phase = "accept" / "resample" calls
-    tslt_verify_accept / tslt_verify_resample (then `out` and `workspace` must be passed to both)."""
+    tslt_verify_accept / tslt_verify_resample (then `out` and `workspace` must be passed to both).
+    first_stage > 0 calls tslt_verify_staged / tslt_verify_accept_staged."""
     lib = load()
     fn = {"both": lib.tslt_verify, "accept": lib.tslt_verify_accept, "resample": lib.tslt_verify_resample}[phase]
+    extra = ()
+    if first_stage and phase != "resample":
+        fn = {"both": lib.tslt_verify_staged, "accept": lib.tslt_verify_accept_staged}[phase]
+        extra = (int(first_stage),)
     _dev(target, name="target")
     if target.dim() != 3:
         raise TsltError("target must be [B, gamma+1, V]")
@@ -244,7 +254,7 @@ def verify(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logi
               _ptr(q_idx), _ptr(q_logit), _ptr(q_count), k_cap, _ptr(draft_tokens), _ptr(u_accept),
               _ptr(u_resample), _ptr(out["accept_len"]), _ptr(out["tokens"]), _ptr(out.get("ratio")),
               _ptr(out.get("beta")), _ptr(out.get("status")), _ptr(ws), ws.numel() if ws is not None else 0,
-              _stream()))
+              _stream(), *extra))
     return out
 
 

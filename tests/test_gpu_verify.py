@@ -125,6 +125,60 @@ def test_verify_rows_outside_the_exp_table(tslt, dtype):
     print(dtype, P.compare_verify(out, v, label="table-edges"), v["accept_len"])
 
 
+@pytest.mark.parametrize("name,base,kw,first_stage", [
+    ("bf16-g8-s1", "chain_topk", dict(B=24, V=20011), 1),       # stages of 1, 1, 2, 4 positions
+    ("bf16-g8-s3", "chain_topp", dict(B=16), 3),                # 3, 3, 2 (the last stage is cut at gamma)
+    ("f32-g3-s2", "tiny", dict(B=6, V=5003, gamma=3), 2),
+    ("f16-g16-s2", "stress", dict(B=4, gamma=16, V=30000, dtype="f16"), 2),
+    ("bf16-g8-s8", "chain_topk", dict(B=4, V=9001), 8),         # first_stage = gamma: the plain call
+])
+def test_verify_in_stages(tslt, name, base, kw, first_stage):
+    """tslt_verify_staged: decisions and tokens are those of tslt_verify and of the oracle; ratio and beta
+    agree with tslt_verify wherever the staged call evaluated the position and are NaN elsewhere, and a
+    position is skipped exactly if an earlier stage holds a rejection."""
+    w = W.scaled(W.WORKLOADS[base], **kw)
+    chain = W.make_chain(w, 13, DEV)
+    u_acc = chain["u_accept"].clone()
+    u_acc[0] = 0.0                                    # one sequence that accepts everything
+    chain["u_accept"] = u_acc
+    ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), w.T, w.top_k, w.top_p, w.k_cap,
+                         P.to_np(chain["u_sample"]), P.to_np(u_acc), P.to_np(chain["u_resample"]))
+    args = [chain["target"], w.T, t32(ref["q_idx"]), t32(ref["q_logit"]), t32(ref["q_count"]), t32(ref["tokens"]),
+            u_acc, chain["u_resample"]]
+    plain = tslt.verify(*args)
+    staged = tslt.verify(*args, first_stage=first_stage)
+    torch.cuda.synchronize()
+    for k in ("accept_len", "tokens", "status"):
+        assert torch.equal(plain[k], staged[k]), (name, k)
+    # which positions the staged call looked at
+    G = w.gamma
+    bounds, j0, ln, k = [], 0, (first_stage if first_stage < G else G), 0
+    while j0 < G:
+        c = min(ln, G - j0)
+        bounds.append((j0, j0 + c))
+        j0 += c
+        if k > 0:
+            ln *= 2
+        k += 1
+    n = P.to_np(plain["accept_len"])
+    pr, sr = P.to_np(plain["ratio"]), P.to_np(staged["ratio"])
+    pb, sb = P.to_np(plain["beta"]), P.to_np(staged["beta"])
+    skipped = 0
+    for b in range(w.B):
+        for (a, e) in bounds:
+            looked = a <= n[b]                        # no rejection before this stage
+            for j in range(a, e):
+                if looked:
+                    assert np.array_equal(sr[b, j], pr[b, j], equal_nan=True) and np.array_equal(sb[b, j], pb[b, j], equal_nan=True), (name, b, j)
+                else:
+                    assert np.isnan(sr[b, j]) and np.isnan(sb[b, j]), (name, b, j)
+                    skipped += 1
+    print(name, P.compare_verify(staged, ref["verify"], label=name), "positions skipped", skipped, "of", w.B * G)
+    assert n[0] == G
+    if first_stage < G:
+        assert skipped > 0
+
+
 def test_verify_argument_errors(tslt):
     w = W.scaled(W.WORKLOADS["chain_topk"], B=2, V=3000, gamma=2)
     chain = W.make_chain(w, 3, DEV)
