@@ -301,6 +301,8 @@ def main():
     if not is_tree and plan.first_stage > 0:
         # rows after a rejection are not read: the all-rows byte count does not describe this run
         res["hbm_GBps_whole_step"] = res["hbm_frac_whole_step"] = None
+        if "verify_accept" in kernels:
+            kernels["verify_accept"]["GBps"] = None
     elif not is_tree and not args.no_staged:
         # beside the headline (every position evaluated): the same steps with the acceptance tests taken in
         # two stages, which does not read the target rows behind a rejection found in the first half
