@@ -38,10 +38,10 @@ def committed_traffic(workload, kernel):
 class ChainPlan:
     """truncate_sample -> verify_accept -> verify_resample on a chain workload."""
 
-    def __init__(self, w, n_sets, torch, tslt, W, dev):
+    def __init__(self, w, n_sets, torch, tslt, W, dev, sets=None):
         self.w, self.torch, self.tslt = w, torch, tslt
         B, G, V, K = w.B, w.gamma, w.V, w.k_cap
-        self.sets = [W.make_chain(w, 100 + i, dev) for i in range(n_sets)]
+        self.sets = sets if sets is not None else [W.make_chain(w, 100 + i, dev) for i in range(n_sets)]
         self.first_stage = 0
         i32, f32 = torch.int32, torch.float32
         # preallocated outputs and workspace: nothing is allocated inside the timed region
@@ -319,6 +319,35 @@ def main():
         res["staged_acceptance"] = {"first_stage": max(1, w.gamma // 2), "ms_per_step": round(dt1 / args.steps * 1e3, 4),
                                     "value": round(plan.positions * args.steps / dt1, 1), "unit": "draft positions/s",
                                     "note": "same outputs (accept_len, tokens); ratio and beta of skipped positions are NaN"}
+    if not is_tree and not args.no_staged:
+        # beside the headline (one stream, a step starts when the one before it has ended): the same steps
+        # issued alternately on two streams, each with its own outputs and workspace, as a server with two
+        # batches in flight would; the ramp and the tail of one step's kernels are then covered by the other's
+        plans = [plan, ChainPlan(w, n_sets, torch, tslt, W, dev, sets=sets)]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]         # default priority
+        def run2(n):
+            for i in range(n):
+                with torch.cuda.stream(streams[i % 2]):
+                    for (_, _, fn, _) in plans[i % 2].ops:
+                        fn(sets[i % len(sets)])
+            torch.cuda.synchronize()
+        run2(4)
+        t2 = time.perf_counter()
+        run2(args.steps)
+        dt2 = time.perf_counter() - t2
+        res["two_streams"] = {"ms_per_step": round(dt2 / args.steps * 1e3, 4),
+                              "value": round(plan.positions * args.steps / dt2, 1), "unit": "draft positions/s",
+                              "note": "steps alternate between two streams (two batches in flight); every position evaluated"}
+        for q in plans:
+            q.first_stage = max(1, w.gamma // 2)
+        run2(4)
+        t3 = time.perf_counter()
+        run2(args.steps)
+        dt3 = time.perf_counter() - t3
+        for q in plans:
+            q.first_stage = 0
+        res["two_streams"]["with_staged_acceptance"] = {"ms_per_step": round(dt3 / args.steps * 1e3, 4),
+                                                        "value": round(plan.positions * args.steps / dt3, 1)}
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
