@@ -22,7 +22,8 @@ namespace tslt {
 constexpr int kTruncThreads = 256;   // threads of a truncate workgroup (one row each)
 constexpr int kBatch = 4;        // tiles per batch; the first batch is the threshold sample
 constexpr int kDepth = 2;        // batches in flight per thread during the pass
-constexpr int kRing = 96;      // vectors a wave can park; expanded when a third full
+constexpr int kRing = 96;      // vectors a wave can park
+constexpr int kRingExpand = 58; // expanded when it holds more than this: one pass of 64 lanes, nearly all busy
 
 struct TruncateParams {
   const void* logits;
@@ -480,7 +481,7 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
       const uint32_t head = uint32_t(rs.head);
 
       // Two vectors at a time: their exp2 terms go to the partial sums; a vector with an element above
-      // tau0 is parked in the ring, which is expanded when it is a third full.
+      // tau0 is parked in the ring, which is expanded when it holds about a wave's worth of vectors.
       auto process_pair = [&](const uint4& w0, const uint4& w1, uint32_t vidx0, uint32_t vidx1) {
         float a[E], b[E];
         unpack<T>(w0, a);
@@ -513,7 +514,7 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
           }
           wave_cnt += n_a + __popcll(mask_b);
           lost |= wave_cnt > kRing;                    // some vector found no slot
-          if (wave_cnt > kRing / 3) {                  // wave-uniform
+          if (wave_cnt > kRingExpand) {                // wave-uniform
             expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh);
             wave_cnt = 0;
           }
