@@ -299,8 +299,20 @@ __device__ int two_pass_select(const void* row, const RowSplit& rs, int k_sel, f
 //
 // Expands the n vectors parked in a wave's ring into candidate records (elements above tau0).  Lane s
 // takes slot s: it marks which of the vector's elements are above tau0, a wave scan of the counts gives
-// every lane its place behind a single reservation in the shared candidate array, and the marked elements
-// are written there.
+// every lane its place behind a single reservation in the shared candidate array.  Nearly every slot holds
+// one such element, so they are then written one per round (as many rounds as the fullest slot needs),
+// each read back from the slot by its position, instead of one branch per element position.
+template <typename T> __device__ __forceinline__ float ring_element(const uint4* ring, int slot, int e);
+template <> __device__ __forceinline__ float ring_element<float>(const uint4* ring, int slot, int e) {
+  return reinterpret_cast<const float*>(ring)[slot * 4 + e];
+}
+template <> __device__ __forceinline__ float ring_element<Bf16>(const uint4* ring, int slot, int e) {
+  return as_f32(uint32_t(reinterpret_cast<const uint16_t*>(ring)[slot * 8 + e]) << 16);
+}
+template <> __device__ __forceinline__ float ring_element<F16>(const uint4* ring, int slot, int e) {
+  return f16_lo(reinterpret_cast<const uint16_t*>(ring)[slot * 8 + e]);
+}
+
 template <typename T>
 __device__ __forceinline__ void expand_ring(const uint4* ring, const uint32_t* ring_vidx, int n, float tau0,
                                             uint32_t head, uint64_t* cand, int cap, TruncateShared& sh) {
@@ -308,18 +320,15 @@ __device__ __forceinline__ void expand_ring(const uint4* ring, const uint32_t* r
   const int lane = lane_id();
   for (int s0 = 0; s0 < n; s0 += 64) {
     const int s = s0 + lane;
-    float v[E];
-    uint32_t vi = 0;
-    int cnt = 0;
+    uint32_t mask = 0, vi = 0;          // bit e: element e of this lane's vector is above tau0
     if (s < n) {
+      float v[E];
       unpack<T>(ring[s], v);
       vi = ring_vidx[s];
 #pragma unroll
-      for (int e = 0; e < E; ++e) cnt += v[e] > tau0 ? 1 : 0;
-    } else {
-#pragma unroll
-      for (int e = 0; e < E; ++e) v[e] = -INFINITY;
+      for (int e = 0; e < E; ++e) mask |= v[e] > tau0 ? (1u << e) : 0u;
     }
+    const int cnt = __popc(mask);
     const int incl = wave_incl_scan_i32(cnt);
     const int total = last_lane_i32(incl);
     if (total == 0) continue;
@@ -328,10 +337,12 @@ __device__ __forceinline__ void expand_ring(const uint4* ring, const uint32_t* r
     base = __builtin_amdgcn_readfirstlane(base);
     int pos = base + incl - cnt;
     const uint32_t idx0 = head + vi * E;
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-      if (v[e] > tau0) {
-        if (pos < cap) cand[pos] = make_cand(v[e], idx0 + e);
+    const int rounds = wave_max_i32(cnt);
+    for (int r = 0; r < rounds; ++r) {
+      if (mask != 0) {
+        const int e = __builtin_ctz(mask);
+        mask &= mask - 1;
+        if (pos < cap) cand[pos] = make_cand(ring_element<T>(ring, s, e), idx0 + uint32_t(e));
         ++pos;
       }
     }
