@@ -84,6 +84,27 @@ def test_argument_errors_are_found_on_the_host(lib):
     lib.tslt_sample.argtypes = [vp, vp, vp, i64, i32, vp, i32, i32, vp, vp, vp]
     assert lib.tslt_sample(fake, fake, fake, 4, 2048, fake, 1, 0, fake, None, None) == -2
     assert lib.tslt_sample(None, fake, fake, 4, 16, fake, 1, 0, fake, None, None) == -1
+    # verification: shapes, workspace, the staged call's extra argument
+    verify_args = [vp, ctypes.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tslt_verify.restype = ctypes.c_int
+    lib.tslt_verify.argtypes = verify_args
+    lib.tslt_verify_staged.restype = ctypes.c_int
+    lib.tslt_verify_staged.argtypes = verify_args + [i32]
+    lib.tslt_workspace_bytes.restype = ctypes.c_size_t
+    lib.tslt_workspace_bytes.argtypes = [ctypes.c_int, i64, i64, i64, i32]
+    need = lib.tslt_workspace_bytes(2, 4, 8, 1000, 16)
+    ws = ctypes.c_void_p(0x10000)
+    def verify(fn, B=4, gamma=8, V=1000, stride=1000, T=1.0, cap=16, ws=ws, ws_bytes=need, extra=()):
+        return fn(fake, 1, B, gamma, V, stride, T, fake, fake, fake, cap, fake, fake, fake, fake, fake, None, None, None,
+                  ws, ws_bytes, None, *extra)
+    assert verify(lib.tslt_verify, gamma=0) == -1
+    assert verify(lib.tslt_verify, T=-1.0) == -1
+    assert verify(lib.tslt_verify, cap=2000) == -2
+    assert verify(lib.tslt_verify, ws_bytes=need - 1) == -3 and b"workspace" in lib.tslt_last_error()
+    assert verify(lib.tslt_verify, ws=ctypes.c_void_p(0x10010)) == -3       # workspace not aligned to 256 bytes
+    assert verify(lib.tslt_verify, B=0) == 0
+    assert verify(lib.tslt_verify_staged, extra=(-1,)) == -1 and b"first_stage" in lib.tslt_last_error()
+    assert verify(lib.tslt_verify_staged, B=0, extra=(2,)) == 0
 
 
 def test_exp64_header_matches_libm(tmp_path):
