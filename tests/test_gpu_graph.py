@@ -9,7 +9,8 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def test_captured_round_replays_like_eager(tslt):
+@pytest.mark.parametrize("first_stage", [0, 2])        # tslt_verify, and tslt_verify_staged (one launch per stage)
+def test_captured_round_replays_like_eager(tslt, first_stage):
     w = W.scaled(W.WORKLOADS["chain_topp"], B=12, V=20011, gamma=4)
     B, G, V, K = w.B, w.gamma, w.V, w.k_cap
     sets = [W.make_chain(w, 20 + i, DEV) for i in range(3)]
@@ -19,7 +20,7 @@ def test_captured_round_replays_like_eager(tslt):
     def run(c, tr=None, vf=None):
         tr = tslt.truncate(c["draft"], w.T, w.top_k, w.top_p, K, out=tr, u=c["u_sample"].view(B * G, 1), payload="bf16")
         vf = tslt.verify(c["target"], w.T, tr["idx"].view(B, G, K), tr["logit"].view(B, G, K), tr["count"].view(B, G),
-                         tr["token"].view(B, G), c["u_accept"], c["u_resample"], out=vf, workspace=ws)
+                         tr["token"].view(B, G), c["u_accept"], c["u_resample"], out=vf, workspace=ws, first_stage=first_stage)
         return tr, vf
 
     eager = []
