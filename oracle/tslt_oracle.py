@@ -512,6 +512,47 @@ def verify_tree(target, T, expansion, q_idx, q_logit, q_count, cand_tokens, u_ac
 
 
 # ----------------------------------------------------------------------------------------------
+# Section 3.2: what truncation to the first K entries does to the acceptance rate
+# ----------------------------------------------------------------------------------------------
+def truncation_stats_row(target_row, T, idx, logit, count, k_list) -> dict:
+    """One target row against the nested prefixes of one truncated set.  The set is in canonical order, so
+    its first K entries are the Top-K set of the same draft distribution.  For every K of k_list:
+      keep[K] = sum_{i<K} q_hat_i, the share of the whole set's mass that the prefix holds (q_hat = softmax of
+                the received values over the whole set);
+      beta[K] = sum_x min(q_hat_K(x), p(x)) with q_hat_K the prefix renormalised (the acceptance rate under
+                truncation, Section 3.2; 1 - TV(q_hat_K, p) by Lemma 1).
+    K larger than the set's size means the whole set.  A broken row gives NaN."""
+    target_row = np.asarray(target_row, dtype=np.float32)
+    ks = [int(k) for k in k_list]
+    keep = np.full(len(ks), np.nan)
+    beta = np.full(len(ks), np.nan)
+    st = _row_status(target_row)
+    cnt = int(count)
+    if st != STATUS_OK or cnt <= 0:
+        return dict(keep=keep, beta=beta, status=st if st != STATUS_OK else STATUS_EMPTY)
+    p = dense_probs(target_row, T)
+    qh = sparse_probs(logit, cnt)
+    ids = np.asarray(idx[:cnt], dtype=np.int64)
+    for j, K in enumerate(ks):
+        k = min(max(K, 1), cnt)
+        c = float(np.sum(qh[:k]))
+        keep[j] = c
+        beta[j] = float(np.sum(np.minimum(qh[:k] / c, p[ids[:k]])))
+    return dict(keep=keep, beta=beta, status=STATUS_OK)
+
+
+def truncation_stats(target_rows, T, idx, logit, count, k_list) -> dict:
+    """truncation_stats_row over rows: target_rows [n, V], sets [n, k_cap]."""
+    target_rows = np.asarray(target_rows, dtype=np.float32)
+    n = target_rows.shape[0]
+    out = dict(keep=np.full((n, len(k_list)), np.nan), beta=np.full((n, len(k_list)), np.nan), status=np.zeros(n, np.int32))
+    for r in range(n):
+        one = truncation_stats_row(target_rows[r], T, idx[r], logit[r], count[r], k_list)
+        out["keep"][r], out["beta"][r], out["status"][r] = one["keep"], one["beta"], one["status"]
+    return out
+
+
+# ----------------------------------------------------------------------------------------------
 # Section 2.2: payload model, and the wire format of a batch of truncated sets
 # ----------------------------------------------------------------------------------------------
 def index_bits(V: int) -> int:
