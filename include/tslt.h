@@ -241,6 +241,26 @@ int tslt_verify_accept_staged(const void* target_logits, tslt_dtype dt, int64_t 
                               int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta,
                               int32_t* status, void* ws, size_t ws_bytes, void* stream, int32_t first_stage);
 
+/* What truncation to K entries does to the acceptance rate (Section 3.2).  A set is in canonical order, so
+ * its first K entries are the Top-K set of the same draft distribution; for every K of k_list and every
+ * row, against that row's dense target distribution p:
+ *   out_keep[row, j]  sum of q_hat over the first K entries, q_hat the softmax of the received values over
+ *                     the WHOLE set (times tslt_truncate's out_mass: rho of Theorem 1, the Top-K probability
+ *                     mass of the draft distribution; sigma = 1 - rho)
+ *   out_beta[row, j]  sum_x min(q_hat_K(x), p(x)), q_hat_K the first K entries renormalised: the acceptance
+ *                     rate under truncation, 1 - TV(q_hat_K, p) by Lemma 1; Theorem 1 bounds its distance
+ *                     from the rate under the untruncated q by sigma
+ * K below 1 counts as 1, K above the set's size as the whole set.  A row that is unusable (status bits as for
+ * tslt_verify), or whose set is empty, gives NaN.
+ *   target_logits  [rows, row_stride] device;  q_idx, q_logit [rows, k_cap], q_count [rows] device
+ *   k_list         HOST pointer, n_k values (1 <= n_k <= 32), read before the call returns
+ *   out_keep, out_beta  [rows, n_k] fp32 device;  status [rows] int32 device, may be NULL
+ * No workspace. */
+int tslt_truncation_stats(const void* target_logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
+                          float target_temperature, const int32_t* q_idx, const float* q_logit, const int32_t* q_count,
+                          int32_t k_cap, const int32_t* k_list, int32_t n_k, float* out_keep, float* out_beta,
+                          int32_t* status, void* stream);
+
 /* Token-tree verification (Algorithm 8 with Algorithm 5 at every non-leaf node) for B trees.
  *
  * Nodes are stored breadth-first (Section 4.1): layer l has W_l = k_1*...*k_l nodes, the i-th node of

@@ -14,6 +14,7 @@
 #include "wire.h"
 #include "tree.h"
 #include "verify.h"
+#include "stats.h"
 
 namespace {
 
@@ -298,6 +299,39 @@ int tslt_verify_staged(TSLT_VERIFY_ARGS, int32_t first_stage) {
 }
 int tslt_verify_accept_staged(TSLT_VERIFY_ARGS, int32_t first_stage) {
   return verify_impl(1, first_stage, "tslt_verify_accept_staged", TSLT_VERIFY_PASS);
+}
+
+int tslt_truncation_stats(const void* target_logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
+                          float target_temperature, const int32_t* q_idx, const float* q_logit, const int32_t* q_count,
+                          int32_t k_cap, const int32_t* k_list, int32_t n_k, float* out_keep, float* out_beta,
+                          int32_t* status, void* stream) {
+  const char* name = "tslt_truncation_stats";
+  if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "%s: unknown dtype %d", name, int(dt));
+  if (rows < 0 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "%s: bad shape", name);
+  if (V > 0x7FFFFFFF || rows > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: V and rows must fit 31 bits", name);
+  if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "%s: temperature must be > 0", name);
+  if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "%s: k_cap must be in 1..%d", name, TSLT_MAX_K_CAP);
+  if (n_k < 1 || n_k > tslt::kMaxStatK) return fail(TSLT_ERR_UNSUPPORTED, "%s: between 1 and %d values of K", name, tslt::kMaxStatK);
+  if (!k_list) return fail(TSLT_ERR_INVALID_ARG, "%s: null pointer", name);
+  if (rows == 0) return TSLT_OK;
+  if (!target_logits || !q_idx || !q_logit || !q_count || !out_keep || !out_beta) return fail(TSLT_ERR_INVALID_ARG, "%s: null pointer", name);
+  if (reinterpret_cast<uintptr_t>(target_logits) % elem_bytes(dt)) return fail(TSLT_ERR_INVALID_ARG, "%s: logits not aligned to their element type", name);
+  tslt::StatsParams p{};
+  p.target = target_logits; p.rows = rows; p.V = V; p.row_stride = row_stride;
+  p.rT = reciprocal_temperature(target_temperature);
+  p.k2 = log2e_over_T(p.rT);
+  p.q_idx = q_idx; p.q_logit = q_logit; p.q_count = q_count; p.k_cap = k_cap;
+  p.n_k = n_k;
+  for (int j = 0; j < n_k; ++j) p.k_list[j] = k_list[j];
+  p.out_keep = out_keep; p.out_beta = out_beta; p.status = status;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const dim3 grid{unsigned(rows)}, block{unsigned(tslt::kBlock)};
+  if (dt == TSLT_BF16) hipLaunchKernelGGL(tslt::truncation_stats_kernel<tslt::Bf16>, grid, block, 0, s, p);
+  else if (dt == TSLT_F16) hipLaunchKernelGGL(tslt::truncation_stats_kernel<tslt::F16>, grid, block, 0, s, p);
+  else hipLaunchKernelGGL(tslt::truncation_stats_kernel<float>, grid, block, 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e, name);
+  return TSLT_OK;
 }
 
 int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_t V, int64_t row_stride,

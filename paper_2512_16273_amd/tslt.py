@@ -25,7 +25,7 @@ PAYLOAD = {"f32": 0, "bf16": 1, "f16": 2}       # tslt_dtype codes of the format
 EXPORTS = ("tslt_version", "tslt_last_error", "tslt_workspace_bytes", "tslt_truncate", "tslt_truncate_sample", "tslt_sample",
            "tslt_pack_bound_words", "tslt_pack", "tslt_unpack",
            "tslt_verify", "tslt_verify_accept", "tslt_verify_resample", "tslt_verify_staged", "tslt_verify_accept_staged",
-           "tslt_verify_tree")
+           "tslt_truncation_stats", "tslt_verify_tree")
 
 _lib = None
 
@@ -71,6 +71,8 @@ def load(path: Optional[str] = None):
     for fn in (lib.tslt_verify_staged, lib.tslt_verify_accept_staged):
         fn.restype = c.c_int
         fn.argtypes = [vp, c.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, i32]
+    lib.tslt_truncation_stats.restype = c.c_int
+    lib.tslt_truncation_stats.argtypes = [vp, c.c_int, i64, i64, i64, f32, vp, vp, vp, i32, c.POINTER(i32), i32, vp, vp, vp, vp]
     lib.tslt_verify_tree.restype = c.c_int
     lib.tslt_verify_tree.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, c.POINTER(i32), vp, vp, vp, i32, vp, vp,
                                      vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -255,6 +257,30 @@ def verify(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logi
               _ptr(u_resample), _ptr(out["accept_len"]), _ptr(out["tokens"]), _ptr(out.get("ratio")),
               _ptr(out.get("beta")), _ptr(out.get("status")), _ptr(ws), ws.numel() if ws is not None else 0,
               _stream(), *extra))
+    return out
+
+
+def truncation_stats(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logit: torch.Tensor,
+                     q_count: torch.Tensor, k_list: Sequence[int]) -> dict:
+    """tslt_truncation_stats: target [rows, V]; sets [rows, k_cap]; returns keep, beta [rows, len(k_list)] and
+    status [rows]."""
+    lib = load()
+    _dev(target, name="target")
+    if target.dim() != 2:
+        raise TsltError("target must be [rows, V]")
+    rows, V = target.shape
+    _dev(q_idx, torch.int32, "q_idx"); _dev(q_logit, torch.float32, "q_logit"); _dev(q_count, torch.int32, "q_count")
+    k_cap = q_idx.shape[-1]
+    if q_idx.numel() != rows * k_cap or q_logit.numel() != rows * k_cap or q_count.numel() != rows:
+        raise TsltError("truncation_stats: shapes do not agree")
+    ks = (ctypes.c_int32 * len(k_list))(*[int(k) for k in k_list])
+    dev = target.device
+    out = {"keep": torch.empty(rows, len(k_list), dtype=torch.float32, device=dev),
+           "beta": torch.empty(rows, len(k_list), dtype=torch.float32, device=dev),
+           "status": torch.empty(rows, dtype=torch.int32, device=dev)}
+    _check(lib.tslt_truncation_stats(_ptr(target), _dtype_code(target), rows, V, target.stride(0), float(temperature),
+                                     _ptr(q_idx), _ptr(q_logit), _ptr(q_count), k_cap, ks, len(k_list),
+                                     _ptr(out["keep"]), _ptr(out["beta"]), _ptr(out["status"]), _stream()))
     return out
 
 
