@@ -5,8 +5,8 @@ One step = one pass of the whole hot path over one batch of synthetic logits alr
 Chain workloads (default: benchmark configuration 3, "large_vocab", B=256, gamma=8, V=128256, bf16, T=0.7, top-p 0.9
 with K cap 256): tslt_truncate_sample on every draft row (truncation and the draw of the draft token in
 one launch), tslt_verify_accept on every target row, tslt_verify_resample (residual / bonus token).
-Tree workload ("tree", benchmark configuration 4): tslt_truncate on the draft row of every non-leaf node,
-tslt_sample of its candidates, tslt_verify_tree over the whole tree.
+Tree workload ("tree", benchmark configuration 4): tslt_truncate_sample on the draft row of every non-leaf
+node (truncation and the draws of its candidates in one launch), tslt_verify_tree over the whole tree.
 Independent input sets are rotated so that the 256 MB Infinity Cache cannot serve repeats.
 
 Prints ONE JSON line: positions/s, the roofline of the dominant kernel measured with an event pair per
@@ -121,7 +121,8 @@ class TreePlan:
         self.tr = {"idx": torch.empty(R, K, dtype=i32, device=dev), "logit": torch.empty(R, K, dtype=f32, device=dev),
                    "prob": torch.empty(R, K, dtype=f32, device=dev), "count": torch.empty(R, dtype=i32, device=dev),
                    "mass": torch.empty(R, dtype=f32, device=dev), "status": torch.empty(R, dtype=i32, device=dev)}
-        self.sm = {"token": torch.empty(R, kmax, dtype=i32, device=dev), "slot": torch.empty(R, kmax, dtype=i32, device=dev)}
+        self.tr["token"] = torch.empty(R, kmax, dtype=i32, device=dev)
+        self.tr["slot"] = torch.empty(R, kmax, dtype=i32, device=dev)
         self.vt = {"seq": torch.empty(B, len(w.expansion) + 1, dtype=i32, device=dev), "len": torch.empty(B, dtype=i32, device=dev),
                    "node_token": None, "node_slot": None, "ratio": torch.empty(B, n_nodes - 1, dtype=f32, device=dev),
                    "status": torch.empty(B, dtype=i32, device=dev)}
@@ -135,21 +136,18 @@ class TreePlan:
         # nodes off the path never influence the output); every draft row is needed for its candidates
         path_rows = B * (len(w.expansion) + 1)
         self.ops = [("truncate", "truncate_kernel", self.truncate, R * V * s + sparse),
-                    ("sample", "sample_kernel", self.sample, R * K * 8),
                     ("verify_tree", "tree_lazy_walk_kernel", self.verify, path_rows * V * s + path_rows * K * 8)]
-        self.total_bytes = R * V * s + sparse + R * K * 8 + path_rows * V * s + path_rows * K * 8
+        self.total_bytes = R * V * s + sparse + path_rows * V * s + path_rows * K * 8
         self.describe = (f"{w.name}: B={B} trees, expansion={tuple(w.expansion)} ({n_int} non-leaf of {n_nodes} nodes), V={V} "
                          f"{w.dtype} logits, T={w.T}, top_k={w.top_k}, k_cap={K}, candidates drawn "
                          f"{'without' if w.without_replacement else 'with'} replacement and verified by the matching rule, only "
-                         f"the verified path is sampled; {n_sets} rotating input sets; truncate+sample+verify_tree per step")
+                         f"the verified path is sampled; {n_sets} rotating input sets; truncate_sample+verify_tree per step")
 
     def truncate(self, c):
+        # truncation and the draws of every node's candidates in one launch (tslt_truncate_sample)
         w = self.w
-        self.tslt.truncate(c["draft"], w.T, w.top_k, w.top_p, w.k_cap, out=self.tr)
-
-    def sample(self, c):
-        t = self.tr
-        self.tslt.sample(t["idx"], t["logit"], t["count"], c["u_sample"].view(-1, self.kmax), self.w.without_replacement, out=self.sm)
+        self.tslt.truncate(c["draft"], w.T, w.top_k, w.top_p, w.k_cap, out=self.tr, u=c["u_sample"].view(-1, self.kmax),
+                           without_replacement=w.without_replacement)
 
     def verify(self, c):
         w, t = self.w, self.tr
@@ -157,7 +155,7 @@ class TreePlan:
         # children of node n are the kmax consecutive nodes from 1 + n*kmax: the candidates of all non-leaf nodes,
         # node after node, are the tree's candidate array
         self.tslt.verify_tree(c["target"], w.T, w.expansion, t["idx"].view(B, n_int, K), t["logit"].view(B, n_int, K),
-                              t["count"].view(B, n_int), self.sm["token"].view(B, n_int * self.kmax), c["u_accept"], c["u_resample"],
+                              t["count"].view(B, n_int), t["token"].view(B, n_int * self.kmax), c["u_accept"], c["u_resample"],
                               all_nodes=False, out=self.vt, workspace=self.ws, without_replacement=w.without_replacement)
 
     def cpu_baseline(self, budget_s=20.0):

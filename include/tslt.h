@@ -130,13 +130,14 @@ int tslt_sample(const int32_t* idx, const float* logit, const int32_t* count, in
                 int32_t* out_token, int32_t* out_slot, void* stream);
 
 /* "Sparsify-then-sample" (Solution 1 of Section 3.2) in one launch: tslt_truncate followed by n_samples
- * i.i.d. draws from each row's q_hat (Algorithm 4's candidate draws; n_samples = 1 for a chain), with the
- * same results as tslt_truncate followed by tslt_sample(..., without_replacement = 0).
+ * draws from each row's q_hat (Algorithm 4's candidate draws; n_samples = 1 for a chain), with the same
+ * results as tslt_truncate followed by tslt_sample with the same without_replacement.
  *
  *   arguments up to `status`   as for tslt_truncate
  *   u           [rows, n_samples] fp32 uniforms in [0,1)
  *   n_samples   1..TSLT_MAX_BRANCH
- *   out_token   [rows, n_samples] int32 sampled token ids (-1 if the row's set is empty)
+ *   without_replacement   as for tslt_sample
+ *   out_token   [rows, n_samples] int32 sampled token ids (-1 if the row's set is empty or used up)
  *   out_slot    [rows, n_samples] int32 position of the token inside its set; may be NULL
  * Workspace: none.
  */
@@ -144,8 +145,8 @@ int tslt_truncate_sample(const void* logits, tslt_dtype dt, int64_t rows, int64_
                          float temperature, int32_t top_k, float top_p, int32_t k_cap, tslt_dtype payload,
                          int32_t* out_idx, float* out_logit, float* out_prob, int32_t* out_count,
                          float* out_mass, int32_t* status,
-                         const float* u, int32_t n_samples, int32_t* out_token, int32_t* out_slot,
-                         void* ws, size_t ws_bytes, void* stream);
+                         const float* u, int32_t n_samples, int32_t without_replacement,
+                         int32_t* out_token, int32_t* out_slot, void* ws, size_t ws_bytes, void* stream);
 
 /* Wire format of truncated sets (Section 2.2 fixes the size of the payload, K pairs of a b_idx-bit token id
  * and a b_prob-bit value per position; the layout is defined here).  The stream of one row, least significant

@@ -47,6 +47,7 @@ struct TruncateParams {
   float* out_mass;
   int32_t* status;
   // optional draws from q_hat in the same launch (null u = none)
+  int without_replacement;
   const float* u;    // [rows, n_samples]
   int n_samples;
   int32_t* out_token;
@@ -728,10 +729,13 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
     if (p.status) p.status[row_i] = st;
   }
   // ---- draws from q_hat: the first entry whose inclusive prefix exceeds u * (mass of the kept set) ---
+  // Without replacement a drawn entry's weight becomes 0 and the prefix masses are scanned again, so the
+  // next draw is from the renormalised rest; when nothing is left the draw gives -1.
   if (p.u) {
+    double w_total = count > 0 ? p_total : 0.0;
     for (int c = 0; c < p.n_samples; ++c) {
       const size_t o = size_t(row_i) * p.n_samples + c;
-      const double target = double(p.u[o]) * p_total;
+      const double target = double(p.u[o]) * w_total;
       int not_above = 0, last_pos = -1;
       double run = p_excl;
 #pragma unroll
@@ -743,7 +747,7 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
           if (pw[r] > 0.0) last_pos = i;
         }
       }
-      int slot = count > 0 ? block_sum_i32<NW>(not_above, sh.red) : -1;
+      int slot = w_total > 0.0 ? block_sum_i32<NW>(not_above, sh.red) : -1;
       if (slot >= count) slot = block_max_i32<NW>(last_pos, sh.red);   // only for u >= 1 (uniform branch)
 #pragma unroll
       for (int r = 0; r < kMaxPer; ++r)
@@ -751,6 +755,16 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
       if (tid == 0) {
         if (slot < 0) p.out_token[o] = -1;
         if (p.out_slot) p.out_slot[o] = slot;
+      }
+      if (p.without_replacement && c + 1 < p.n_samples && slot >= 0) {       // uniform
+        double rest = 0.0;
+#pragma unroll
+        for (int r = 0; r < kMaxPer; ++r) {
+          const int i = tid * per + r;
+          if (r < per && i == slot) pw[r] = 0.0;
+          if (r < per && i < count) rest += pw[r];
+        }
+        p_excl = block_excl_scan_f64<NW>(rest, sh.red, w_total);
       }
     }
   }

@@ -115,7 +115,7 @@ size_t tslt_workspace_bytes(int op, int64_t n_outer, int64_t n_inner, int64_t V,
 static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
                          float temperature, int32_t top_k, float top_p, int32_t k_cap, tslt_dtype payload, int32_t* out_idx,
                          float* out_logit, float* out_prob, int32_t* out_count, float* out_mass, int32_t* status,
-                         const float* u, int32_t n_samples, int32_t* out_token, int32_t* out_slot,
+                         const float* u, int32_t n_samples, int32_t without_replacement, int32_t* out_token, int32_t* out_slot,
                          void* ws, size_t ws_bytes, void* stream) {
   if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: unknown dtype %d", int(dt));
   if (rows < 0 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: bad shape rows=%lld V=%lld stride=%lld", (long long)rows, (long long)V, (long long)row_stride);
@@ -138,7 +138,8 @@ static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_
   p.k_sel = (top_k > 0 && top_k < k_cap) ? top_k : k_cap;
   p.out_idx = out_idx; p.out_logit = out_logit; p.out_prob = out_prob; p.out_count = out_count;
   p.out_mass = out_mass; p.status = status;
-  p.u = u; p.n_samples = n_samples; p.out_token = out_token; p.out_slot = out_slot;
+  p.u = u; p.n_samples = n_samples; p.without_replacement = without_replacement ? 1 : 0;
+  p.out_token = out_token; p.out_slot = out_slot;
   constexpr int NT = tslt::kTruncThreads;
   const size_t lds = plan_truncate(dt, V, NT, p);
 
@@ -166,19 +167,19 @@ int tslt_truncate(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, in
                   float* out_logit, float* out_prob, int32_t* out_count, float* out_mass, int32_t* status,
                   void* ws, size_t ws_bytes, void* stream) {
   return truncate_impl(logits, dt, rows, V, row_stride, temperature, top_k, top_p, k_cap, payload, out_idx, out_logit, out_prob,
-                       out_count, out_mass, status, nullptr, 0, nullptr, nullptr, ws, ws_bytes, stream);
+                       out_count, out_mass, status, nullptr, 0, 0, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 int tslt_truncate_sample(const void* logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
                          float temperature, int32_t top_k, float top_p, int32_t k_cap, tslt_dtype payload, int32_t* out_idx,
                          float* out_logit, float* out_prob, int32_t* out_count, float* out_mass, int32_t* status,
-                         const float* u, int32_t n_samples, int32_t* out_token, int32_t* out_slot,
+                         const float* u, int32_t n_samples, int32_t without_replacement, int32_t* out_token, int32_t* out_slot,
                          void* ws, size_t ws_bytes, void* stream) {
   if (n_samples < 1 || n_samples > TSLT_MAX_BRANCH)
     return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate_sample: n_samples must be in 1..%d", TSLT_MAX_BRANCH);
   if (rows > 0 && (!u || !out_token)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate_sample: null pointer");
   return truncate_impl(logits, dt, rows, V, row_stride, temperature, top_k, top_p, k_cap, payload, out_idx, out_logit, out_prob,
-                       out_count, out_mass, status, u, n_samples, out_token, out_slot, ws, ws_bytes, stream);
+                       out_count, out_mass, status, u, n_samples, without_replacement, out_token, out_slot, ws, ws_bytes, stream);
 }
 
 int64_t tslt_pack_bound_words(int64_t rows, int32_t k_cap, int64_t V) {

@@ -62,7 +62,7 @@ def load(path: Optional[str] = None):
     lib.tslt_unpack.argtypes = [vp, vp, i64, i32, i64, c.c_int, vp, vp, vp, vp]
     lib.tslt_truncate_sample.restype = c.c_int
     lib.tslt_truncate_sample.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, f32, i32, c.c_int, vp, vp, vp, vp, vp, vp,
-                                         vp, i32, vp, vp, vp, sz, vp]
+                                         vp, i32, i32, vp, vp, vp, sz, vp]
     lib.tslt_sample.restype = c.c_int
     lib.tslt_sample.argtypes = [vp, vp, vp, i64, i32, vp, i32, i32, vp, vp, vp]
     for fn in (lib.tslt_verify, lib.tslt_verify_accept, lib.tslt_verify_resample):
@@ -138,10 +138,10 @@ def _workspace(nbytes: int, device) -> Optional[torch.Tensor]:
 
 def truncate(logits: torch.Tensor, temperature: float, top_k: int, top_p: float, k_cap: int,
              want_prob: bool = True, out: Optional[dict] = None, u: Optional[torch.Tensor] = None,
-             payload: str = "f32") -> dict:
+             payload: str = "f32", without_replacement: bool = False) -> dict:
     """tslt_truncate over logits [..., V].  Returns idx, logit, prob, count, mass, status ([rows, k_cap] /
     [rows]).  With uniforms u [rows, n] it is tslt_truncate_sample: the result also holds token, slot
-    [rows, n], n i.i.d. draws from each row's q_hat.  payload = "bf16" / "f16" rounds the kept values to the
+    [rows, n], n draws from each row's q_hat (i.i.d., or without replacement).  payload = "bf16" / "f16" rounds the kept values to the
     format in which they will travel before q_hat and the draws are computed."""
     lib = load()
     _dev(logits, name="logits", contiguous=False)
@@ -170,7 +170,8 @@ def truncate(logits: torch.Tensor, temperature: float, top_k: int, top_p: float,
     _check(lib.tslt_truncate_sample(_ptr(logits), _dtype_code(logits), rows, V, stride, float(temperature), int(top_k),
                                     float(top_p), int(k_cap), PAYLOAD[payload], _ptr(out["idx"]), _ptr(out["logit"]),
                                     _ptr(out.get("prob")), _ptr(out["count"]), _ptr(out.get("mass")),
-                                    _ptr(out.get("status")), _ptr(u2), n, _ptr(out["token"]), _ptr(out.get("slot")),
+                                    _ptr(out.get("status")), _ptr(u2), n, 1 if without_replacement else 0,
+                                    _ptr(out["token"]), _ptr(out.get("slot")),
                                     None, 0, _stream()))
     return out
 

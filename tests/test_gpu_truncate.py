@@ -119,20 +119,26 @@ def test_sample_matches_oracle(tslt, wo):
     ("bf16-k1024-2", 70000, 6, 1.0, 0, 0.999, 1024, 2),
     ("bf16-k3-16", 9000, 5, 1.0, 3, 0.0, 4, 16),
     ("f16-topp-2", 32000, 12, 0.8, 0, 0.95, 256, 2),
+    ("f32-topk-4-wor", 151936, 6, 1.0, 32, 0.0, 32, 4),       # benchmark configuration 4's draws
+    ("bf16-k3-16-wor", 9000, 5, 1.0, 3, 0.0, 4, 16),           # more draws than entries: the rest give -1
+    ("bf16-topp-5-wor", 32000, 12, 0.8, 0, 0.95, 256, 5),
 ])
 def test_truncate_sample_in_one_launch(tslt, name, V, rows, T, top_k, top_p, k_cap, n):
     """tslt_truncate_sample: the truncation against the oracle as for tslt_truncate; the draws against the
     oracle's sampling from the very sets the call returned, and against tslt_sample on those sets."""
+    wor = name.endswith("-wor")
     w = W.scaled(W.WORKLOADS["chain_topk"], V=V, dtype=name.split("-")[0])
     z = rows_like(w, rows, 21)
     u = W.uniforms((rows, n), 9, 2, 3, DEV)
-    out = tslt.truncate(z, T, top_k, top_p, k_cap, u=u)
+    out = tslt.truncate(z, T, top_k, top_p, k_cap, u=u, without_replacement=wor)
     torch.cuda.synchronize()
     P.compare_truncate({k: v for k, v in out.items() if k not in ("token", "slot")}, z, T, top_k, top_p, k_cap, label=name)
-    want = O.sample(P.to_np(out["idx"]), P.to_np(out["logit"]), P.to_np(out["count"]), P.to_np(u), False)
+    want = O.sample(P.to_np(out["idx"]), P.to_np(out["logit"]), P.to_np(out["count"]), P.to_np(u), wor)
+    if name == "bf16-k3-16-wor":
+        assert np.all(want["slot"][:, 3:] == -1) and np.all(want["slot"][:, :3] >= 0)
     assert np.array_equal(P.to_np(out["slot"]), want["slot"]), name
     assert np.array_equal(P.to_np(out["token"]), want["token"]), name
-    two = tslt.sample(out["idx"], out["logit"], out["count"], u, False)
+    two = tslt.sample(out["idx"], out["logit"], out["count"], u, wor)
     assert torch.equal(two["token"], out["token"]) and torch.equal(two["slot"], out["slot"])
 
 
