@@ -762,19 +762,25 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const
       if (sub >= 0) {
         // ---- level 3: which element of that run; thread t owns kPerT consecutive elements ------------
         const int64_t run_first = seg_first_elem + int64_t(sub) * kRun;
+        // a thread's kPerT elements are one vector of the run; it is requested before the corrections are
+        // laid out, so that it travels meanwhile
+        static_assert(kPerT == E, "a thread's share of a run is one vector");
+        const int64_t my_vec = seg_first_vec + int64_t(sub) * kRunVecs + tid;
+        uint4 dv = neg_inf_vec<T>();
+        if (my_vec < rs.nvec) dv = load_vec(&rs.body[my_vec]);
 #pragma unroll
         for (int k = 0; k < kMaxPer; ++k)
           if (yi[k] >= run_first && yi[k] < run_first + kRun) elem_corr[yi[k] - run_first] = corr[k];
         __syncthreads();
+        float tv[E];
+        unpack<T>(dv, tv);
         double v[kPerT];
         double mine = 0.0;
 #pragma unroll
         for (int q = 0; q < kPerT; ++q) {
-          const int64_t y = run_first + tid * kPerT + q;
           v[q] = 0.0;
-          if ((y - rs.head) / E < rs.nvec) {
-            const float t = load_elem<T>(row, y);
-            v[q] = exp64(double(__fmul_rn(t, rT)) - double(smax)) + elem_corr[tid * kPerT + q];
+          if (my_vec < rs.nvec) {
+            v[q] = exp64(double(__fmul_rn(tv[q], rT)) - double(smax)) + elem_corr[tid * kPerT + q];
             if (v[q] < 0.0) v[q] = 0.0;
           }
           mine += v[q];
