@@ -346,6 +346,25 @@ def main():
             q.first_stage = 0
         res["two_streams"]["with_staged_acceptance"] = {"ms_per_step": round(dt3 / args.steps * 1e3, 4),
                                                         "value": round(plan.positions * args.steps / dt3, 1)}
+    if not args.copy_calibration:
+        # what this chip delivers to a kernel that only reads (same load shape as the dense passes): the practical
+        # ceiling beside the published peak.  2048 chunks of 256 KiB, three buffers in turn, events on this stream
+        bufs = [torch.ones(1 << 29, dtype=torch.uint8, device=dev) for _ in range(3)]
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        for i in range(6):
+            tslt.calibrate_read(bufs[i % 3], 2048, sink)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n_cal = 30
+        e0.record()
+        for i in range(n_cal):
+            tslt.calibrate_read(bufs[i % 3], 2048, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        cal = (1 << 29) * n_cal / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        res["read_ceiling"] = {"GBps": round(cal, 1), "frac_of_peak": round(cal / HBM_PEAK_GBS, 4),
+                               "dominant_kernel_frac": round(roofline["achieved"] / cal, 4) if roofline else None,
+                               "note": "tslt_calibrate_read: read-only kernel, 16-byte nontemporal loads, 512 MiB per launch"}
+        del bufs
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)

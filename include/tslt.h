@@ -242,6 +242,14 @@ int tslt_verify_accept_staged(const void* target_logits, tslt_dtype dt, int64_t 
                               int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta,
                               int32_t* status, void* ws, size_t ws_bytes, void* stream, int32_t first_stage);
 
+/* Measurement aid, not part of the method: one read-only streaming launch over `bytes` bytes of `src` with
+ * the load shape of the dense passes (n_blocks workgroups of 256 threads, each reading one contiguous chunk
+ * with 16-byte nontemporal loads, four in flight per thread).  Timed by the caller, it gives the read
+ * bandwidth this chip delivers to a kernel that only reads: the practical ceiling beside the published peak.
+ *   src     device, 16-byte aligned;  bytes a positive multiple of n_blocks * 16384
+ *   sink    device, one uint32 (written only if the xor-sum of the data equals a fixed constant) */
+int tslt_calibrate_read(const void* src, size_t bytes, int32_t n_blocks, uint32_t* sink, void* stream);
+
 /* What truncation to K entries does to the acceptance rate (Section 3.2).  A set is in canonical order, so
  * its first K entries are the Top-K set of the same draft distribution; for every K of k_list and every
  * row, against that row's dense target distribution p:

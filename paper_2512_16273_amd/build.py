@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libtslt.so")
 SOURCES = [os.path.join(HERE, "csrc", "tslt.hip")]
-HEADERS = [os.path.join(HERE, "csrc", n) for n in ("common.h", "truncate.h", "sample.h", "verify.h", "rowops.h", "exp64.h", "tree.h", "wire.h", "stats.h")] + \
+HEADERS = [os.path.join(HERE, "csrc", n) for n in ("common.h", "truncate.h", "sample.h", "verify.h", "rowops.h", "exp64.h", "tree.h", "wire.h", "stats.h", "calib.h")] + \
           [os.path.join(ROOT, "include", "tslt.h")]
 
 

@@ -15,6 +15,7 @@
 #include "tree.h"
 #include "verify.h"
 #include "stats.h"
+#include "calib.h"
 
 namespace {
 
@@ -300,6 +301,22 @@ int tslt_verify_staged(TSLT_VERIFY_ARGS, int32_t first_stage) {
 }
 int tslt_verify_accept_staged(TSLT_VERIFY_ARGS, int32_t first_stage) {
   return verify_impl(1, first_stage, "tslt_verify_accept_staged", TSLT_VERIFY_PASS);
+}
+
+int tslt_calibrate_read(const void* src, size_t bytes, int32_t n_blocks, uint32_t* sink, void* stream) {
+  const char* name = "tslt_calibrate_read";
+  if (!src || !sink) return fail(TSLT_ERR_INVALID_ARG, "%s: null pointer", name);
+  if (reinterpret_cast<uintptr_t>(src) % 16) return fail(TSLT_ERR_INVALID_ARG, "%s: the buffer must be 16-byte aligned", name);
+  if (n_blocks < 1) return fail(TSLT_ERR_INVALID_ARG, "%s: n_blocks must be >= 1", name);
+  const size_t chunk = size_t(16) * tslt::kCalibUnroll * tslt::kBlock;       // bytes one workgroup reads per round
+  if (bytes == 0 || bytes % (chunk * size_t(n_blocks)) != 0)
+    return fail(TSLT_ERR_INVALID_ARG, "%s: bytes must be a positive multiple of n_blocks * %zu", name, chunk);
+  const uint64_t vecs_per_block = bytes / 16 / size_t(n_blocks);
+  hipLaunchKernelGGL(tslt::calibrate_read_kernel, dim3(unsigned(n_blocks)), dim3(tslt::kBlock), 0,
+                     reinterpret_cast<hipStream_t>(stream), reinterpret_cast<const uint4*>(src), vecs_per_block, sink);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e, name);
+  return TSLT_OK;
 }
 
 int tslt_truncation_stats(const void* target_logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,

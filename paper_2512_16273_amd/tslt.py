@@ -25,7 +25,7 @@ PAYLOAD = {"f32": 0, "bf16": 1, "f16": 2}       # tslt_dtype codes of the format
 EXPORTS = ("tslt_version", "tslt_last_error", "tslt_workspace_bytes", "tslt_truncate", "tslt_truncate_sample", "tslt_sample",
            "tslt_pack_bound_words", "tslt_pack", "tslt_unpack",
            "tslt_verify", "tslt_verify_accept", "tslt_verify_resample", "tslt_verify_staged", "tslt_verify_accept_staged",
-           "tslt_truncation_stats", "tslt_verify_tree")
+           "tslt_truncation_stats", "tslt_calibrate_read", "tslt_verify_tree")
 
 _lib = None
 
@@ -71,6 +71,8 @@ def load(path: Optional[str] = None):
     for fn in (lib.tslt_verify_staged, lib.tslt_verify_accept_staged):
         fn.restype = c.c_int
         fn.argtypes = [vp, c.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, i32]
+    lib.tslt_calibrate_read.restype = c.c_int
+    lib.tslt_calibrate_read.argtypes = [vp, sz, i32, vp, vp]
     lib.tslt_truncation_stats.restype = c.c_int
     lib.tslt_truncation_stats.argtypes = [vp, c.c_int, i64, i64, i64, f32, vp, vp, vp, i32, c.POINTER(i32), i32, vp, vp, vp, vp]
     lib.tslt_verify_tree.restype = c.c_int
@@ -259,6 +261,12 @@ def verify(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logi
               _ptr(out.get("beta")), _ptr(out.get("status")), _ptr(ws), ws.numel() if ws is not None else 0,
               _stream(), *extra))
     return out
+
+
+def calibrate_read(src: torch.Tensor, n_blocks: int, sink: torch.Tensor) -> None:
+    """tslt_calibrate_read: one read-only streaming launch over the whole of `src` (time it from outside)."""
+    _dev(src, name="src"); _dev(sink, name="sink")
+    _check(load().tslt_calibrate_read(_ptr(src), src.numel() * src.element_size(), int(n_blocks), _ptr(sink), _stream()))
 
 
 def truncation_stats(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logit: torch.Tensor,

@@ -103,3 +103,19 @@ def test_device_to_server_round_over_the_wire(tslt):
                          P.to_np(rx["count"]).reshape(B, G), P.to_np(tr["token"]).reshape(B, G), P.to_np(c["u_accept"]),
                          P.to_np(c["u_resample"]))
     print(P.compare_verify(vf, ref, label="wire"))
+
+
+def test_calibrate_read_runs_and_checks_its_arguments(tslt):
+    """The measurement aid: a read-only launch over a buffer; sizes that do not split into whole rounds are refused."""
+    buf = torch.ones(64 * 16384, dtype=torch.uint8, device=DEV)
+    sink = torch.zeros(1, dtype=torch.int32, device=DEV)
+    tslt.calibrate_read(buf, 64, sink)
+    tslt.calibrate_read(buf, 1, sink)
+    torch.cuda.synchronize()
+    assert int(sink[0]) == 0                                  # the xor-sum of this data is not the constant
+    with pytest.raises(tslt.TsltError):
+        tslt.calibrate_read(buf, 48, sink)                    # 64 rounds do not split over 48 workgroups
+    with pytest.raises(tslt.TsltError):
+        tslt.calibrate_read(buf[:1000], 1, sink)
+    with pytest.raises(tslt.TsltError):
+        tslt.calibrate_read(buf[8:8 + 16384], 1, sink)        # not 16-byte aligned
