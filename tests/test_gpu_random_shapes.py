@@ -19,7 +19,7 @@ def t32(a):
 @pytest.mark.parametrize("stream", [0, 1, 2, 3])
 def test_random_chain_rounds(tslt, stream):
     rng = np.random.default_rng(1000 + stream)
-    totals = dict(sequences=0, accept_near_ties=0, top_p_near_ties=0)
+    totals = dict(sequences=0, accept_near_ties=0, accept_near_tie_mismatches=0, top_p_near_ties=0, top_p_near_tie_mismatches=0)
     for case in range(12):
         dtype = ["f32", "bf16", "f16"][rng.integers(3)]
         V = int(rng.choice([rng.integers(50, 3000), rng.integers(3000, 40000), rng.integers(40000, 90000)]))
@@ -46,7 +46,7 @@ def test_random_chain_rounds(tslt, stream):
                                  label=f"case {stream}.{case}")
         ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), T, top_k, top_p, k_cap,
                              P.to_np(chain["u_sample"]), P.to_np(chain["u_accept"]), P.to_np(chain["u_resample"]))
-        if res["top_p_near_ties"] == 0:
+        if res["top_p_near_tie_mismatches"] == 0:
             assert np.array_equal(P.to_np(tr["token"]).reshape(B, gamma), ref["tokens"]), case
         args = [chain["target"], T, t32(ref["q_idx"]), t32(ref["q_logit"]), t32(ref["q_count"]), t32(ref["tokens"]),
                 chain["u_accept"], chain["u_resample"]]
@@ -57,6 +57,8 @@ def test_random_chain_rounds(tslt, stream):
         for k in ("accept_len", "tokens", "status"):
             assert torch.equal(out[k], staged[k]), (case, k)
         totals["sequences"] += B
-        totals["accept_near_ties"] += r["accept_near_ties"]
+        for k in ("accept_near_ties", "accept_near_tie_mismatches"):
+            totals[k] += r[k]
+        totals["top_p_near_tie_mismatches"] += res["top_p_near_tie_mismatches"]
         totals["top_p_near_ties"] += res["top_p_near_ties"]
     print(totals)

@@ -15,7 +15,7 @@ DEV = "cuda:0"
 @pytest.mark.parametrize("stream", [0, 1, 2])
 def test_random_trees(tslt, stream):
     rng = np.random.default_rng(2000 + stream)
-    totals = dict(trees=0, near_tie_nodes=0, near_tie_sequences=0)
+    totals = dict(trees=0, near_tie_nodes=0, near_tie_node_mismatches=0, near_tie_sequences=0)
     for case in range(8):
         dtype = ["f32", "bf16", "f16"][rng.integers(3)]
         depth = int(rng.integers(1, 5))

@@ -61,7 +61,7 @@ def test_round_truncate_sample_verify(tslt):
     ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), w.T, w.top_k, w.top_p, w.k_cap,
                          P.to_np(chain["u_sample"]), P.to_np(chain["u_accept"]), P.to_np(chain["u_resample"]))
     t = P.compare_truncate(tr, chain["draft"].reshape(B * G, V), w.T, w.top_k, w.top_p, w.k_cap, label="round")
-    if t["top_p_near_ties"] == 0:
+    if t["top_p_near_tie_mismatches"] == 0:
         assert np.array_equal(P.to_np(smp["token"]).reshape(B, G), ref["tokens"])
         print(P.compare_verify(out, ref["verify"], label="round"))
 
@@ -225,3 +225,53 @@ def test_large_vocab_full_size_sampled_sequences(tslt):
     assert torch.all(tk[:, :G][pos[:, :G] < n[:, None]] == toks.long()[pos[:, :G] < n[:, None]])
     assert torch.all(out["status"] == 0)
     print("mean accepted length", float(n.float().mean()))
+
+
+def test_stress_configuration_at_its_own_shape(tslt):
+    """Benchmark configuration 5 with its own V = 256000, k_cap = 1024, gamma = 16, bf16, T = 1.0, top-p 0.99 (the
+    launch plan of the truncation kernel -- sample fraction, threshold rank, candidate capacity, LDS carve-up --
+    follows from V and k_cap, so a smaller V does not reach it), on B = 2 sequences: 32 draft and 34 target
+    rows through tslt_truncate_sample, tslt_verify_accept + tslt_verify_resample and tslt_verify_staged, the
+    calls `bench.py --workload stress` makes, against the oracle."""
+    w = W.scaled(W.WORKLOADS["stress"], B=2)
+    assert (w.V, w.k_cap, w.gamma, w.dtype, w.T, w.top_p) == (256000, 1024, 16, "bf16", 1.0, 0.99)
+    chain = W.make_chain(w, 5, DEV)
+    B, G, V, K = w.B, w.gamma, w.V, w.k_cap
+    rows = chain["draft"].view(B * G, V)
+    tr = tslt.truncate(rows, w.T, w.top_k, w.top_p, K, u=chain["u_sample"].view(B * G, 1))
+    torch.cuda.synchronize()
+    res = P.compare_truncate({k: v for k, v in tr.items() if k not in ("token", "slot")}, rows, w.T, w.top_k, w.top_p, K,
+                             label="stress")
+    print({k: v for k, v in res.items() if k != "ref"}, "counts", P.to_np(tr["count"]).min(), P.to_np(tr["count"]).max())
+    # the single-pass selection has to carry this shape: no row on the multi-pass path
+    assert res["exact_path_rows"] == 0
+    ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), w.T, w.top_k, w.top_p, K,
+                         P.to_np(chain["u_sample"]), P.to_np(chain["u_accept"]), P.to_np(chain["u_resample"]))
+    if res["top_p_near_tie_mismatches"] == 0:
+        assert np.array_equal(P.to_np(tr["token"]).reshape(B, G), ref["tokens"])
+    # verification on the GPU's own sets and tokens where they are the oracle's (always, short of a near tie)
+    args = [chain["target"], w.T, t32(ref["q_idx"]), t32(ref["q_logit"]), t32(ref["q_count"]), t32(ref["tokens"]),
+            chain["u_accept"], chain["u_resample"]]
+    ws = torch.empty(tslt.workspace_bytes(tslt.OP_VERIFY, B, G, V, K), dtype=torch.uint8, device=DEV)
+    split = tslt.verify(*args, workspace=ws, phase="accept")
+    tslt.verify(*args, out=split, workspace=ws, phase="resample")
+    whole = tslt.verify(*args)
+    torch.cuda.synchronize()
+    for k in whole:
+        assert torch.equal(whole[k], split[k]) or k in ("ratio", "beta") and torch.allclose(whole[k], split[k], equal_nan=True), k
+    print(P.compare_verify(whole, ref["verify"], label="stress"), "accept_len", ref["verify"]["accept_len"])
+    for first_stage in (1, G // 2):
+        staged = tslt.verify(*args, first_stage=first_stage)
+        torch.cuda.synchronize()
+        for k in ("accept_len", "tokens", "status"):
+            assert torch.equal(whole[k], staged[k]), (first_stage, k)
+        P.compare_verify(staged, ref["verify"], label=f"stress staged {first_stage}")
+    # a sequence that accepts every position reaches the bonus row at this shape too
+    u0 = torch.zeros_like(chain["u_accept"])
+    args[6] = u0
+    ref_all = O.verify_chain(P.to_np(chain["target"]), w.T, ref["q_idx"], ref["q_logit"], ref["q_count"], ref["tokens"],
+                             P.to_np(u0), P.to_np(chain["u_resample"]))
+    out_all = tslt.verify(*args, first_stage=1)
+    torch.cuda.synchronize()
+    assert np.all(ref_all["accept_len"] == G)
+    print(P.compare_verify(out_all, ref_all, label="stress all accepted"))
