@@ -78,7 +78,8 @@ def test_verify_forced_paths_and_broken_rows(tslt):
     chain["target"] = target
     u_acc = chain["u_accept"].clone()
     u_acc[0] = 0.0                            # sequence 0: everything accepted -> bonus token
-    u_acc[1] = 0.99999994                     # sequence 1: rejected wherever ratio < 1
+    u_acc[1] = 0.9995                         # sequence 1: rejected wherever ratio < 0.9995 (a uniform within 1e-6 of 1 would
+                                              # put every ratio >= 1 inside the near-tie window)
     u_acc[5] = 0.0
     chain["u_accept"] = u_acc
     ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(target), w.T, w.top_k, w.top_p, w.k_cap,
@@ -114,7 +115,9 @@ def test_verify_rows_outside_the_exp_table(tslt, dtype):
     target[4, :, 5::11] = 490.0
     chain["target"] = target.to(chain["target"].dtype)
     u_acc = chain["u_accept"].clone()
-    u_acc[:, 0] = 0.99999994                           # reject at once wherever the ratio is below 1
+    # reject at once wherever the ratio is below 0.9995 (a uniform within 1e-6 of 1 would put every ratio >= 1
+    # inside the near-tie window)
+    u_acc[:, 0] = 0.9995
     chain["u_accept"] = u_acc
     ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), w.T, w.top_k, w.top_p, w.k_cap,
                          P.to_np(chain["u_sample"]), P.to_np(u_acc), P.to_np(chain["u_resample"]))
