@@ -11,7 +11,7 @@
  * Conventions that hold for every entry point
  *   - Every pointer is a DEVICE pointer owned by the caller unless it is marked "host".  The library
  *     allocates nothing: scratch memory comes from a caller-provided workspace sized by
- *     tslt_workspace_bytes() and aligned to 256 bytes.
+ *     tslt_workspace_bytes() and aligned to 256 bytes (tslt_verify_static alone uses an array of its own).
  *   - `stream` is a hipStream_t passed as void*.  Calls enqueue kernels on it and return without
  *     synchronising; outputs are valid once the stream has reached that point.
  *   - Return value: TSLT_OK, or a negative code for an error found on the host (bad argument,
@@ -241,6 +241,26 @@ int tslt_verify_accept_staged(const void* target_logits, tslt_dtype dt, int64_t 
                               const int32_t* draft_tokens, const float* u_accept, const float* u_resample,
                               int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta,
                               int32_t* status, void* ws, size_t ws_bytes, void* stream, int32_t first_stage);
+
+/* tslt_verify for callers that cannot allocate or bring a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments as tslt_verify without `ws` / `ws_bytes`, same
+ * kernels, same results; the per-position decisions and status words (8 bytes per draft position) live in an
+ * array that is part of the library's device image (TSLT_STATIC_MAX_POSITIONS positions, 2 MiB per GPU, held
+ * until the process ends).  The call allocates nothing and calls no allocating routine.
+ *   - B * gamma above TSLT_STATIC_MAX_POSITIONS returns TSLT_ERR_UNSUPPORTED (use tslt_verify and a workspace).
+ *   - The first call on a device looks up the array's address on that device (hipGetSymbolAddress) and keeps
+ *     it; make that first call outside a stream capture.
+ *   - Every call on one GPU uses that GPU's one array, and the array keeps what the last call left in it
+ *     (each call overwrites every word it reads later, nothing needs clearing).  Two calls that overlap in time
+ *     on one GPU -- on different streams, or from different threads -- race: serialise them, or use tslt_verify
+ *     with one workspace per call in flight. */
+#define TSLT_STATIC_MAX_POSITIONS 262144
+int tslt_verify_static(const void* target_logits, tslt_dtype dt, int64_t B, int32_t gamma, int64_t V,
+                       int64_t row_stride, float target_temperature,
+                       const int32_t* q_idx, const float* q_logit, const int32_t* q_count, int32_t k_cap,
+                       const int32_t* draft_tokens, const float* u_accept, const float* u_resample,
+                       int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta,
+                       int32_t* status, void* stream);
 
 /* Measurement aid, not part of the method: one read-only streaming launch over `bytes` bytes of `src` with
  * the load shape of the dense passes (n_blocks workgroups of 256 threads, each reading one contiguous chunk

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 #include <string>
 
 #include "common.h"
@@ -16,6 +17,12 @@
 #include "verify.h"
 #include "stats.h"
 #include "calib.h"
+
+// Scratch memory of tslt_verify_static: the per-position decisions and status words that tslt_verify keeps in
+// its caller's workspace.  Every GPU the library runs on holds its own copy until the process ends.  In host
+// code the name is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+#define TSLT_STATIC_SCRATCH_BYTES (2 * 4 * TSLT_STATIC_MAX_POSITIONS)
+static __device__ __align__(256) unsigned char scratch[TSLT_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -83,6 +90,27 @@ size_t plan_truncate(tslt_dtype dt, int64_t V, int nt, tslt::TruncateParams& p) 
     }
   }
   return tslt::truncate_lds_bytes(p.ring_bytes, p.lds_recs);
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+hipError_t scratch_on_current_device(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
 }
 
 template <typename K> hipError_t allow_large_lds(K kernel) {
@@ -301,6 +329,28 @@ int tslt_verify_staged(TSLT_VERIFY_ARGS, int32_t first_stage) {
 }
 int tslt_verify_accept_staged(TSLT_VERIFY_ARGS, int32_t first_stage) {
   return verify_impl(1, first_stage, "tslt_verify_accept_staged", TSLT_VERIFY_PASS);
+}
+
+int tslt_verify_static(const void* target_logits, tslt_dtype dt, int64_t B, int32_t gamma, int64_t V, int64_t row_stride,
+                       float target_temperature, const int32_t* q_idx, const float* q_logit, const int32_t* q_count,
+                       int32_t k_cap, const int32_t* draft_tokens, const float* u_accept, const float* u_resample,
+                       int32_t* out_accept_len, int32_t* out_tokens, float* out_ratio, float* out_beta, int32_t* status,
+                       void* stream) {
+  const char* name = "tslt_verify_static";
+  if (B < 0 || gamma < 1) return fail(TSLT_ERR_INVALID_ARG, "%s: bad shape", name);
+  if (B > TSLT_STATIC_MAX_POSITIONS || B * int64_t(gamma) > TSLT_STATIC_MAX_POSITIONS)
+    return fail(TSLT_ERR_UNSUPPORTED, "%s: B * gamma = %lld positions, the static scratch array holds %d; use tslt_verify "
+                "with a workspace", name, (long long)(B * int64_t(gamma)), TSLT_STATIC_MAX_POSITIONS);
+  if (tslt::verify_workspace_bytes(B, gamma, V, k_cap) > size_t(TSLT_STATIC_SCRATCH_BYTES))
+    return fail(TSLT_ERR_UNSUPPORTED, "%s: the static scratch array is too small for this call", name);
+  void* ptr = nullptr;
+  const hipError_t e = scratch_on_current_device(&ptr);
+  if (e != hipSuccess) return hip_fail(e, "tslt_verify_static: address of the scratch array");
+  // every position's decision and status word is written by the acceptance kernel before the resampling
+  // kernel reads it, so nothing in the array has to start at zero
+  return verify_impl(3, 0, name, target_logits, dt, B, gamma, V, row_stride, target_temperature, q_idx, q_logit, q_count,
+                     k_cap, draft_tokens, u_accept, u_resample, out_accept_len, out_tokens, out_ratio, out_beta, status, ptr,
+                     size_t(TSLT_STATIC_SCRATCH_BYTES), stream);
 }
 
 int tslt_calibrate_read(const void* src, size_t bytes, int32_t n_blocks, uint32_t* sink, void* stream) {

@@ -25,7 +25,7 @@ PAYLOAD = {"f32": 0, "bf16": 1, "f16": 2}       # tslt_dtype codes of the format
 EXPORTS = ("tslt_version", "tslt_last_error", "tslt_workspace_bytes", "tslt_truncate", "tslt_truncate_sample", "tslt_sample",
            "tslt_pack_bound_words", "tslt_pack", "tslt_unpack",
            "tslt_verify", "tslt_verify_accept", "tslt_verify_resample", "tslt_verify_staged", "tslt_verify_accept_staged",
-           "tslt_truncation_stats", "tslt_calibrate_read", "tslt_verify_tree")
+           "tslt_verify_static", "tslt_truncation_stats", "tslt_calibrate_read", "tslt_verify_tree")
 
 _lib = None
 
@@ -71,6 +71,8 @@ def load(path: Optional[str] = None):
     for fn in (lib.tslt_verify_staged, lib.tslt_verify_accept_staged):
         fn.restype = c.c_int
         fn.argtypes = [vp, c.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, i32]
+    lib.tslt_verify_static.restype = c.c_int
+    lib.tslt_verify_static.argtypes = [vp, c.c_int, i64, i32, i64, i64, f32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.tslt_calibrate_read.restype = c.c_int
     lib.tslt_calibrate_read.argtypes = [vp, sz, i32, vp, vp]
     lib.tslt_truncation_stats.restype = c.c_int
@@ -260,6 +262,36 @@ def verify(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logi
               _ptr(u_resample), _ptr(out["accept_len"]), _ptr(out["tokens"]), _ptr(out.get("ratio")),
               _ptr(out.get("beta")), _ptr(out.get("status")), _ptr(ws), ws.numel() if ws is not None else 0,
               _stream(), *extra))
+    return out
+
+
+STATIC_MAX_POSITIONS = 262144
+
+
+def verify_static(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logit: torch.Tensor,
+                  q_count: torch.Tensor, draft_tokens: torch.Tensor, u_accept: torch.Tensor, u_resample: torch.Tensor,
+                  out: dict) -> dict:
+    """tslt_verify_static: tslt_verify without a workspace (the library's own static device array holds the
+    per-position decisions).  `out` must hold preallocated accept_len, tokens, ratio, beta, status tensors: this
+    wrapper allocates nothing either."""
+    lib = load()
+    _dev(target, name="target")
+    if target.dim() != 3:
+        raise TsltError("target must be [B, gamma+1, V]")
+    B, g1, V = target.shape
+    gamma = g1 - 1
+    _dev(q_idx, torch.int32, "q_idx"); _dev(q_logit, torch.float32, "q_logit"); _dev(q_count, torch.int32, "q_count")
+    _dev(draft_tokens, torch.int32, "draft_tokens"); _dev(u_accept, torch.float32, "u_accept")
+    _dev(u_resample, torch.float32, "u_resample")
+    k_cap = q_idx.shape[-1]
+    if q_idx.numel() != B * gamma * k_cap or u_resample.numel() != B * g1 or u_accept.numel() != B * gamma:
+        raise TsltError("verify_static: shapes do not agree")
+    if out["accept_len"].numel() != B or out["tokens"].numel() != B * g1:
+        raise TsltError("verify_static: output shapes do not agree")
+    _check(lib.tslt_verify_static(_ptr(target), _dtype_code(target), B, gamma, V, target.stride(1), float(temperature),
+                                  _ptr(q_idx), _ptr(q_logit), _ptr(q_count), k_cap, _ptr(draft_tokens), _ptr(u_accept),
+                                  _ptr(u_resample), _ptr(out["accept_len"]), _ptr(out["tokens"]), _ptr(out.get("ratio")),
+                                  _ptr(out.get("beta")), _ptr(out.get("status")), _stream()))
     return out
 
 
