@@ -553,6 +553,52 @@ def truncation_stats(target_rows, T, idx, logit, count, k_list) -> dict:
 
 
 # ----------------------------------------------------------------------------------------------
+# Section 4.3: acceptance rates of the k candidates of multi-candidate verification
+# ----------------------------------------------------------------------------------------------
+def multi_candidate_rates(p, q_idx, q_prob, k: int) -> dict:
+    """beta^(j), j = 1..k, and the total acceptance rate theta of Section 4.3 for one node, under Algorithm 5
+    as printed (candidates i.i.d. from q_hat, the same q_hat at every stage).  P^(1) = P and
+    p^(j+1) = norm(max(0, p^(j) - q_hat)) do not depend on which tokens were drawn, so the rates are functions
+    of (p, q_hat) alone:
+      beta^(j) = sum_x min(q_hat(x), p^(j)(x))                       (the lemma of Section 4.3)
+      theta    = beta^(1) + sum_{i=2..k} beta^(i) prod_{j<i} (1 - beta^(j)).
+    A stage whose residual is empty (beta^(j) = 1: the candidate is always accepted) ends the recursion; the
+    rates of the stages after it, which are never reached, are NaN and add nothing to theta."""
+    p_j = np.asarray(p, dtype=np.float64).copy()
+    q_hat = scatter_sparse(p_j.shape[0], np.asarray(q_idx, dtype=np.int64), q_prob)
+    beta = np.full(int(k), np.nan)
+    theta = 0.0
+    reach = 1.0                                  # probability that stage j is reached: prod_{i<j} (1 - beta^(i))
+    for j in range(int(k)):
+        beta[j] = float(np.sum(np.minimum(q_hat, p_j)))
+        theta += beta[j] * reach
+        reach *= 1.0 - beta[j]
+        r = np.maximum(0.0, p_j - q_hat)
+        Zr = float(np.sum(r))
+        if not (Zr > 0.0):
+            break
+        p_j = r / Zr
+    return dict(beta=beta, theta=theta)
+
+
+def multi_candidate_stats(target_rows, T, idx, logit, count, k: int) -> dict:
+    """multi_candidate_rates over rows: target_rows [n, V] against truncated sets [n, k_cap] (p = softmax of the
+    scaled target row, q_hat = softmax of the received values).  A broken row or an empty set gives NaN."""
+    target_rows = np.asarray(target_rows, dtype=np.float32)
+    n = target_rows.shape[0]
+    out = dict(beta=np.full((n, int(k)), np.nan), theta=np.full(n, np.nan), status=np.zeros(n, np.int32))
+    for r in range(n):
+        st = _row_status(target_rows[r])
+        cnt = int(count[r])
+        if st != STATUS_OK or cnt <= 0:
+            out["status"][r] = st if st != STATUS_OK else STATUS_EMPTY
+            continue
+        one = multi_candidate_rates(dense_probs(target_rows[r], T), np.asarray(idx[r][:cnt]), sparse_probs(logit[r], cnt), k)
+        out["beta"][r], out["theta"][r] = one["beta"], one["theta"]
+    return out
+
+
+# ----------------------------------------------------------------------------------------------
 # Section 2.2: payload model, and the wire format of a batch of truncated sets
 # ----------------------------------------------------------------------------------------------
 def index_bits(V: int) -> int:
