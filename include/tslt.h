@@ -27,6 +27,10 @@
  *   - Order of a truncated set ("canonical order"): raw logit descending, ties by ascending token
  *     index.  Logits equal to -inf have probability 0 and are never selected; NaN or +inf marks the
  *     row TSLT_ROW_NONFINITE.
+ *   - A truncated set handed to the server side (q_idx, q_logit, q_count) must hold DISTINCT token indices in
+ *     [0, V) and finite values, none more than 700 above the first (tslt_truncate writes them in descending
+ *     order, so its sets always qualify).  A value that is not finite or an index outside the vocabulary is
+ *     found and reported as TSLT_ROW_BAD_SET; repeated indices are not looked for (they would be counted twice).
  *   - Sampling is inverse-CDF with caller-supplied uniforms u in [0,1): the first bucket whose
  *     cumulative weight exceeds u * total, accumulated in fp64.  Dense distributions are scanned in
  *     ascending token index, sparse ones in canonical order.  Uniforms are indexed by position /
@@ -58,6 +62,8 @@ enum {
   TSLT_ROW_NONFINITE = 1,        /* NaN or +inf among the logits of a row that was needed */
   TSLT_ROW_EMPTY = 2,            /* no logit above -inf, or an empty sparse set */
   TSLT_ROW_TOKEN_NOT_IN_SET = 4, /* a draft token / candidate that is not in its sparse set: rejected */
+  TSLT_ROW_BAD_SET = 8,          /* a received set with a value that is not finite or an index outside [0, V): the
+                                    position counts as unusable (as for TSLT_ROW_NONFINITE) */
   TSLT_ROW_EXACT_PATH = 256      /* informational: the row took the multi-pass selection path */
 };
 
@@ -289,6 +295,25 @@ int tslt_truncation_stats(const void* target_logits, tslt_dtype dt, int64_t rows
                           float target_temperature, const int32_t* q_idx, const float* q_logit, const int32_t* q_count,
                           int32_t k_cap, const int32_t* k_list, int32_t n_k, float* out_keep, float* out_beta,
                           int32_t* status, void* stream);
+
+/* Acceptance rates of multi-candidate verification with k candidates per position (Section 4.3), for Algorithm 5
+ * as printed (candidates i.i.d. from q_hat, the same q_hat at every stage).  P^(1) = P and the residual update
+ * p^(j+1) = norm(max(0, p^(j) - q_hat)) do not depend on which tokens were drawn, so for every row, against
+ * that row's dense target distribution p:
+ *   out_beta[row, j]  beta^(j+1) = sum_x min(q_hat(x), p^(j+1)(x)), the rate at which candidate j+1 is accepted
+ *                     given that the ones before it were rejected (the lemma of Section 4.3); NaN for the
+ *                     stages behind one whose residual is empty (beta = 1: they are never reached)
+ *   out_theta[row]    theta = beta^(1) + sum_{i=2..k} beta^(i) prod_{j<i} (1 - beta^(j)): the rate at which one
+ *                     of the k candidates is accepted
+ * A row that is unusable (status bits as for tslt_verify), or whose set is empty, gives NaN.
+ *   target_logits  [rows, row_stride] device;  q_idx, q_logit [rows, k_cap], q_count [rows] device
+ *   k              1..TSLT_MAX_BRANCH
+ *   out_beta       [rows, k] fp32 device;  out_theta [rows] fp32 device;  status [rows] int32 device, may be NULL
+ * No workspace. */
+int tslt_multicandidate_stats(const void* target_logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
+                              float target_temperature, const int32_t* q_idx, const float* q_logit,
+                              const int32_t* q_count, int32_t k_cap, int32_t k, float* out_beta, float* out_theta,
+                              int32_t* status, void* stream);
 
 /* Token-tree verification (Algorithm 8 with Algorithm 5 at every non-leaf node) for B trees.
  *

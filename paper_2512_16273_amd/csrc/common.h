@@ -3,7 +3,39 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace tslt {
+
+// ---- host side: what is looked up or set once per device, so that a call after the first on a device is
+// nothing but argument checks and launches ----------------------------------------------------------------
+constexpr int kMaxDevices = 64;
+inline int current_device_slot() {
+  int d = 0;
+  if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) d = 0;
+  return d;
+}
+// Lets `Kernel` be launched with up to `bytes` of dynamic LDS on the current device (needed above 48 KB).
+template <auto Kernel> inline hipError_t allow_dynamic_lds(int bytes) {
+  static std::atomic<int> granted[kMaxDevices];
+  const int d = current_device_slot();
+  if (granted[d].load(std::memory_order_relaxed) >= bytes) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) granted[d].store(bytes, std::memory_order_relaxed);
+  return e;
+}
+// Compute units of the current device (256 if the query fails).
+inline int compute_units() {
+  static std::atomic<int> cus[kMaxDevices];
+  const int d = current_device_slot();
+  int n = cus[d].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+    n = 256;
+  cus[d].store(n, std::memory_order_relaxed);
+  return n;
+}
 
 constexpr int kBlock = 256;            // threads per workgroup of the streaming kernels
 constexpr int kWaves = kBlock / 64;

@@ -22,15 +22,19 @@ constexpr int kSubChunks = kWaves;                  // runs per segment
 constexpr int kAccDepth = 3;                        // batches in flight per thread in eval_row_on_set
 constexpr int kSetPer = 1024 / kBlock;              // set entries per thread (TSLT_MAX_K_CAP / kBlock)
 
+constexpr int kRowBadSet = 8;      // TSLT_ROW_BAD_SET
+
 struct SegResult {       // one segment (or edge piece) of a row that is being sampled
   double sum;            // sum of exp(s - smax) over the piece
   float smax;            // largest scaled logit of the piece (-inf if empty)
   int bad;               // NaN or +inf seen
 };
 
-inline int row_segments(int64_t V) {
-  // body vectors are at most V / 4 (fp32); one more segment covers a ragged end
-  const int64_t nvec_max = V / 4 + 1;
+// Segments of a row of V elements, `per_vec` of them in a 16-byte vector (4 for fp32, the default, which
+// bounds every type and sizes the workspaces; 8 for the 16-bit types).
+inline int row_segments(int64_t V, int per_vec = 4) {
+  // one more segment covers a ragged end
+  const int64_t nvec_max = V / per_vec + 1;
   return int((nvec_max + kSegVecsTotal - 1) / kSegVecsTotal);
 }
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -86,13 +90,7 @@ template <typename T> inline bool exp_table_usable(float rT) {
 }
 
 // Workgroups of a sweep launch: a few per compute unit, each looping over its share of the segments.
-inline int64_t sweep_grid_limit() {
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-    cus = 256;
-  return int64_t(cus) * 4;
-}
+inline int64_t sweep_grid_limit() { return int64_t(compute_units()) * 4; }
 
 template <typename T> __device__ __forceinline__ double exp_table_entry(int i, float rT) {
   using TB = ExpTab<T>;
@@ -162,7 +160,8 @@ __device__ __forceinline__ double table_vec_sum(const uint4& d, const double* ta
 //   p_s, q_s  target and draft probability of the entry (0 where the entry is unused)
 //   yi        token index of the entry, -1 if unused or out of range
 //   p_out     target mass outside the set
-//   ok / st   false with TSLT_ROW_* bits when the row is unusable (NaN, +inf, nothing above -inf)
+//   ok / st   false with TSLT_ROW_* bits when the row is unusable (NaN, +inf, nothing above -inf) or the set is
+//             (a value that is not finite, an index outside the vocabulary)
 // ---------------------------------------------------------------------------------------------
 // log2 of a softmax term relative to the reference c: one fma with k2 = fl32(log2(e) / T).  (The
 // definition rounds s = t / T to fp32 first; not doing so here moves a term by at most 2^-24 of its
@@ -314,7 +313,10 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
     const int i = tid + k * kBlock;
     p_s[k] = 0.0; q_s[k] = 0.0;
     if (i < count) {
-      q_s[k] = exp64(double(ql[i]) - ql0);
+      // a received value that is not finite, or a token index outside the vocabulary, makes the set unusable:
+      // its weight is NaN, which shows in the sum below
+      const float qv = ql[i];
+      q_s[k] = (fabsf(qv) < INFINITY && yi[k] >= 0) ? exp64(double(qv) - ql0) : __longlong_as_double(0x7FF8000000000000ll);
       sum_w += q_s[k];
       if (yi[k] >= 0 && tv[k] > -INFINITY && ok) {
         p_s[k] = exp64(double(__fmul_rn(tv[k], rT)) - double(s_ref));
@@ -326,6 +328,7 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
   sum_e = block_sum_f64<kWaves>(sum_e, sh.red);
   sum_t32 = block_sum_f64<kWaves>(sum_t32, sh.red);
   sum_w = block_sum_f64<kWaves>(sum_w, sh.red);
+  if (sum_w != sum_w) { st |= kRowBadSet; ok = false; }
   double tail = z_c - sum_t32;
   if (tail < 0.0) tail = 0.0;
   tail *= exp2(double(c_ref) - double(vref) * double(k2));   // to the reference of the fp64 terms

@@ -113,10 +113,7 @@ hipError_t scratch_on_current_device(void** out) {
   return hipSuccess;
 }
 
-template <typename K> hipError_t allow_large_lds(K kernel) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             int(kMaxLds - 4096));
-}
+constexpr int kLargeLds = int(kMaxLds - 4096);
 
 }  // namespace
 
@@ -178,13 +175,13 @@ static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_
   (void)ws; (void)ws_bytes;
   const dim3 grid{unsigned(rows)}, block{unsigned(NT)};
   if (dt == TSLT_BF16) {
-    if (big_lds && (e = allow_large_lds(&tslt::truncate_kernel<tslt::Bf16, NT>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    if (big_lds && (e = tslt::allow_dynamic_lds<&tslt::truncate_kernel<tslt::Bf16, NT>>(kLargeLds)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
     hipLaunchKernelGGL((tslt::truncate_kernel<tslt::Bf16, NT>), grid, block, lds, s, p);
   } else if (dt == TSLT_F16) {
-    if (big_lds && (e = allow_large_lds(&tslt::truncate_kernel<tslt::F16, NT>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    if (big_lds && (e = tslt::allow_dynamic_lds<&tslt::truncate_kernel<tslt::F16, NT>>(kLargeLds)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
     hipLaunchKernelGGL((tslt::truncate_kernel<tslt::F16, NT>), grid, block, lds, s, p);
   } else {
-    if (big_lds && (e = allow_large_lds(&tslt::truncate_kernel<float, NT>)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
+    if (big_lds && (e = tslt::allow_dynamic_lds<&tslt::truncate_kernel<float, NT>>(kLargeLds)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
     hipLaunchKernelGGL((tslt::truncate_kernel<float, NT>), grid, block, lds, s, p);
   }
   if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "tslt_truncate launch");
@@ -282,7 +279,8 @@ static int verify_impl(int phases, int stage0, const char* name, const void* tar
   if (V > 0x7FFFFFFF || B * (int64_t(gamma) + 1) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: sizes must fit 31 bits", name);
   if (gamma > 4096) return fail(TSLT_ERR_UNSUPPORTED, "%s: gamma > 4096", name);
   if (stage0 < 0) return fail(TSLT_ERR_INVALID_ARG, "%s: first_stage must be >= 0", name);
-  if (tslt::row_segments(V) + 2 > tslt::kBlock) return fail(TSLT_ERR_UNSUPPORTED, "%s: V too large", name);
+  if (tslt::row_segments(V, 16 / elem_bytes(dt)) + 2 > tslt::kBlock)
+    return fail(TSLT_ERR_UNSUPPORTED, "%s: V too large (at most %d elements of this type)", name, (tslt::kBlock - 2) * tslt::kSegVecsTotal * (16 / elem_bytes(dt)) - 16);
   if (B * int64_t(tslt::row_segments(V)) > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: B too large", name);
   if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "%s: temperature must be > 0", name);
   if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "%s: k_cap must be in 1..%d", name, TSLT_MAX_K_CAP);
@@ -402,6 +400,35 @@ int tslt_truncation_stats(const void* target_logits, tslt_dtype dt, int64_t rows
   return TSLT_OK;
 }
 
+int tslt_multicandidate_stats(const void* target_logits, tslt_dtype dt, int64_t rows, int64_t V, int64_t row_stride,
+                              float target_temperature, const int32_t* q_idx, const float* q_logit, const int32_t* q_count,
+                              int32_t k_cap, int32_t k, float* out_beta, float* out_theta, int32_t* status, void* stream) {
+  const char* name = "tslt_multicandidate_stats";
+  if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "%s: unknown dtype %d", name, int(dt));
+  if (rows < 0 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "%s: bad shape", name);
+  if (V > 0x7FFFFFFF || rows > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: V and rows must fit 31 bits", name);
+  if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "%s: temperature must be > 0", name);
+  if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "%s: k_cap must be in 1..%d", name, TSLT_MAX_K_CAP);
+  if (k < 1 || k > TSLT_MAX_BRANCH) return fail(TSLT_ERR_UNSUPPORTED, "%s: between 1 and %d candidates", name, TSLT_MAX_BRANCH);
+  if (rows == 0) return TSLT_OK;
+  if (!target_logits || !q_idx || !q_logit || !q_count || !out_beta || !out_theta) return fail(TSLT_ERR_INVALID_ARG, "%s: null pointer", name);
+  if (reinterpret_cast<uintptr_t>(target_logits) % elem_bytes(dt)) return fail(TSLT_ERR_INVALID_ARG, "%s: logits not aligned to their element type", name);
+  tslt::McStatsParams p{};
+  p.target = target_logits; p.rows = rows; p.V = V; p.row_stride = row_stride;
+  p.rT = reciprocal_temperature(target_temperature);
+  p.k2 = log2e_over_T(p.rT);
+  p.q_idx = q_idx; p.q_logit = q_logit; p.q_count = q_count; p.k_cap = k_cap; p.k = k;
+  p.out_beta = out_beta; p.out_theta = out_theta; p.status = status;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const dim3 grid{unsigned(rows)}, block{unsigned(tslt::kBlock)};
+  if (dt == TSLT_BF16) hipLaunchKernelGGL(tslt::multicandidate_stats_kernel<tslt::Bf16>, grid, block, 0, s, p);
+  else if (dt == TSLT_F16) hipLaunchKernelGGL(tslt::multicandidate_stats_kernel<tslt::F16>, grid, block, 0, s, p);
+  else hipLaunchKernelGGL(tslt::multicandidate_stats_kernel<float>, grid, block, 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e, name);
+  return TSLT_OK;
+}
+
 int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_t V, int64_t row_stride,
                      float target_temperature, int32_t depth, const int32_t* expansion, const int32_t* q_idx,
                      const float* q_logit, const int32_t* q_count, int32_t k_cap, const int32_t* cand_tokens,
@@ -415,7 +442,7 @@ int tslt_verify_tree(const void* target_logits, tslt_dtype dt, int64_t B, int64_
   if (depth > TSLT_MAX_TREE_DEPTH) return fail(TSLT_ERR_UNSUPPORTED, "%s: depth > %d", name, TSLT_MAX_TREE_DEPTH);
   if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "%s: temperature must be > 0", name);
   if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "%s: k_cap must be in 1..%d", name, TSLT_MAX_K_CAP);
-  if (tslt::row_segments(V) + 2 > tslt::kBlock || V > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: V too large", name);
+  if (tslt::row_segments(V, 16 / elem_bytes(dt)) + 2 > tslt::kBlock || V > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: V too large", name);
   tslt::TreeParams p{};
   int64_t width = 1, n_nodes = 1;
   p.offsets[0] = 0;

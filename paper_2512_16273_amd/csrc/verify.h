@@ -383,10 +383,7 @@ template <typename T> hipError_t launch_verify(VerifyParams p, hipStream_t s, in
   if (phases & 2) {
     p.use_table = exp_table_usable<T>(p.rT) ? 1 : 0;
     const size_t lds = p.use_table ? ExpTab<T>::kBytes : 0;
-    if (lds > 48 * 1024 &&
-        (e = hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_resample_kernel<T>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, int(lds))) != hipSuccess)
-      return e;
+    if (lds > 48 * 1024 && (e = allow_dynamic_lds<&verify_resample_kernel<T>>(int(lds))) != hipSuccess) return e;
     hipLaunchKernelGGL(verify_resample_kernel<T>, dim3(unsigned(p.B)), dim3(kResThreads), lds, s, p);
     e = hipGetLastError();
   }

@@ -18,14 +18,14 @@ LIB_PATH = os.path.join(_HERE, "libtslt.so")
 
 F32, BF16, F16 = 0, 1, 2
 OP_TRUNCATE, OP_SAMPLE, OP_VERIFY, OP_VERIFY_TREE, OP_VERIFY_TREE_PATH = 0, 1, 2, 3, 4
-ROW_NONFINITE, ROW_EMPTY, ROW_TOKEN_NOT_IN_SET, ROW_EXACT_PATH = 1, 2, 4, 256
+ROW_NONFINITE, ROW_EMPTY, ROW_TOKEN_NOT_IN_SET, ROW_BAD_SET, ROW_EXACT_PATH = 1, 2, 4, 8, 256
 MAX_K_CAP = 1024
 PAYLOAD = {"f32": 0, "bf16": 1, "f16": 2}       # tslt_dtype codes of the formats a payload can travel in
 
 EXPORTS = ("tslt_version", "tslt_last_error", "tslt_workspace_bytes", "tslt_truncate", "tslt_truncate_sample", "tslt_sample",
            "tslt_pack_bound_words", "tslt_pack", "tslt_unpack",
            "tslt_verify", "tslt_verify_accept", "tslt_verify_resample", "tslt_verify_staged", "tslt_verify_accept_staged",
-           "tslt_verify_static", "tslt_truncation_stats", "tslt_calibrate_read", "tslt_verify_tree")
+           "tslt_verify_static", "tslt_truncation_stats", "tslt_multicandidate_stats", "tslt_calibrate_read", "tslt_verify_tree")
 
 _lib = None
 
@@ -77,6 +77,8 @@ def load(path: Optional[str] = None):
     lib.tslt_calibrate_read.argtypes = [vp, sz, i32, vp, vp]
     lib.tslt_truncation_stats.restype = c.c_int
     lib.tslt_truncation_stats.argtypes = [vp, c.c_int, i64, i64, i64, f32, vp, vp, vp, i32, c.POINTER(i32), i32, vp, vp, vp, vp]
+    lib.tslt_multicandidate_stats.restype = c.c_int
+    lib.tslt_multicandidate_stats.argtypes = [vp, c.c_int, i64, i64, i64, f32, vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.tslt_verify_tree.restype = c.c_int
     lib.tslt_verify_tree.argtypes = [vp, c.c_int, i64, i64, i64, f32, i32, c.POINTER(i32), vp, vp, vp, i32, vp, vp,
                                      vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -322,6 +324,29 @@ def truncation_stats(target: torch.Tensor, temperature: float, q_idx: torch.Tens
     _check(lib.tslt_truncation_stats(_ptr(target), _dtype_code(target), rows, V, target.stride(0), float(temperature),
                                      _ptr(q_idx), _ptr(q_logit), _ptr(q_count), k_cap, ks, len(k_list),
                                      _ptr(out["keep"]), _ptr(out["beta"]), _ptr(out["status"]), _stream()))
+    return out
+
+
+def multicandidate_stats(target: torch.Tensor, temperature: float, q_idx: torch.Tensor, q_logit: torch.Tensor,
+                         q_count: torch.Tensor, k: int) -> dict:
+    """tslt_multicandidate_stats: target [rows, V]; sets [rows, k_cap]; returns beta [rows, k], theta [rows] and
+    status [rows]."""
+    lib = load()
+    _dev(target, name="target")
+    if target.dim() != 2:
+        raise TsltError("target must be [rows, V]")
+    rows, V = target.shape
+    _dev(q_idx, torch.int32, "q_idx"); _dev(q_logit, torch.float32, "q_logit"); _dev(q_count, torch.int32, "q_count")
+    k_cap = q_idx.shape[-1]
+    if q_idx.numel() != rows * k_cap or q_logit.numel() != rows * k_cap or q_count.numel() != rows:
+        raise TsltError("multicandidate_stats: shapes do not agree")
+    dev = target.device
+    out = {"beta": torch.empty(rows, int(k), dtype=torch.float32, device=dev),
+           "theta": torch.empty(rows, dtype=torch.float32, device=dev),
+           "status": torch.empty(rows, dtype=torch.int32, device=dev)}
+    _check(lib.tslt_multicandidate_stats(_ptr(target), _dtype_code(target), rows, V, target.stride(0), float(temperature),
+                                         _ptr(q_idx), _ptr(q_logit), _ptr(q_count), k_cap, int(k), _ptr(out["beta"]),
+                                         _ptr(out["theta"]), _ptr(out["status"]), _stream()))
     return out
 
 

@@ -63,7 +63,7 @@ def compare_truncate(gpu: dict, logits_rows, T, top_k, top_p, k_cap, rows=None, 
     exact_path = int(np.count_nonzero(g["status"] & 256))
     for r in range(n):
         tag = f"{label} row {rows[r]}"
-        assert (g["status"][r] & 7) == ref["status"][r], (tag, g["status"][r], ref["status"][r])
+        assert (g["status"][r] & 15) == ref["status"][r], (tag, g["status"][r], ref["status"][r])
         if g["count"][r] != ref["count"][r]:
             # only a Top-rho decision at its boundary may differ, and then by the boundary element
             assert ref["margin_rho"][r] < NEAR_TIE, (tag, g["count"][r], ref["count"][r], ref["margin_rho"][r])
@@ -108,7 +108,7 @@ def compare_verify(gpu: dict, ref: dict, seqs=None, label=""):
         assert g["accept_len"][b] == n, (tag, g["accept_len"][b], n, ref["ratio"][b], g.get("ratio", [None])[b])
         assert np.array_equal(g["tokens"][b], ref["tokens"][b]), (tag, g["tokens"][b], ref["tokens"][b],
                                                                   ref["cdf_margin"][b])
-        assert (g["status"][b] & 7) == ref["status"][b], (tag, g["status"][b], ref["status"][b])
+        assert (g["status"][b] & 15) == ref["status"][b], (tag, g["status"][b], ref["status"][b])
         if "ratio" in g and ref["status"][b] == 0:
             rr = ref["ratio"][b, :examined]
             np.testing.assert_allclose(g["ratio"][b, :examined], rr, rtol=RTOL, atol=1e-30, err_msg=tag)
@@ -193,7 +193,7 @@ def compare_tree(gpu: dict, ref: dict, expansion, all_nodes=True, label=""):
             assert np.array_equal(g["node_token"][b][okn], v["node_token"][b][okn]), \
                 (tag, np.nonzero(g["node_token"][b] != v["node_token"][b])[0][:8])
             if not excused.any():
-                assert (g["status"][b] & 7) == v["status"][b], (tag, g["status"][b], v["status"][b])
+                assert (g["status"][b] & 15) == v["status"][b], (tag, g["status"][b], v["status"][b])
             differ_nodes += int(excused.sum())
             seq_excused = any(excused[n] for n in v["path"][b])
         else:

@@ -278,3 +278,26 @@ def test_stress_configuration_at_its_own_shape(tslt):
     torch.cuda.synchronize()
     assert np.all(ref_all["accept_len"] == G)
     print(P.compare_verify(out_all, ref_all, label="stress all accepted"))
+
+
+def test_verify_reports_a_malformed_received_set(tslt):
+    """A received value that is not finite, or a token index outside the vocabulary, marks the position
+    TSLT_ROW_BAD_SET: it counts as unusable (no token from it), the sequences around it are untouched."""
+    w = W.scaled(W.WORKLOADS["chain_topk"], B=5, V=9001, gamma=3)
+    chain = W.make_chain(w, 17, DEV)
+    u_acc = torch.zeros_like(chain["u_accept"])               # every usable position accepts
+    ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), w.T, w.top_k, w.top_p, w.k_cap,
+                         P.to_np(chain["u_sample"]), P.to_np(u_acc), P.to_np(chain["u_resample"]))
+    q_idx, q_logit = t32(ref["q_idx"]), t32(ref["q_logit"])
+    q_logit[1, 1, 3] = float("inf")
+    q_logit[2, 0, 5] = float("nan")
+    q_idx[3, 2, 7] = w.V                                       # one past the vocabulary
+    out = tslt.verify(chain["target"], w.T, q_idx, q_logit, t32(ref["q_count"]), t32(ref["tokens"]), u_acc, chain["u_resample"])
+    torch.cuda.synchronize()
+    n, st, tok = P.to_np(out["accept_len"]), P.to_np(out["status"]), P.to_np(out["tokens"])
+    assert n.tolist() == [3, 1, 0, 2, 3]
+    assert (st & tslt.ROW_BAD_SET != 0).tolist() == [False, True, True, True, False]
+    for b, j in ((1, 1), (2, 0), (3, 2)):
+        assert tok[b, j] == -1 and np.all(tok[b, :j] == ref["tokens"][b, :j])
+    P.compare_verify({k: v[[0, 4]] for k, v in out.items()},
+                     {k: v[[0, 4]] for k, v in ref["verify"].items()}, label="untouched")
