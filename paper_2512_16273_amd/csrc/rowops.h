@@ -19,7 +19,12 @@ constexpr int kSegVecs = 4;                         // 16-byte vectors per threa
 constexpr int kSegVecsTotal = kSegVecs * kBlock;    // vectors per segment
 constexpr int kRunVecs = kSegVecs * 64;             // a run: the consecutive vectors one wave holds
 constexpr int kSubChunks = kWaves;                  // runs per segment
-constexpr int kAccDepth = 3;                        // batches in flight per thread in eval_row_on_set
+// eval_row_on_set keeps kAccDepth batches of kAccVecs 16-byte vectors in flight per thread.  Its kernels ask for
+// eight waves per SIMD (64 registers): 2048 rows of the headline shape are then resident at once, eight
+// workgroups per compute unit, instead of 1280 followed by a thinly occupied second round.
+constexpr int kAccDepth = 4;
+constexpr int kAccVecs = 2;
+constexpr int kAccWavesPerSimd = 8;
 constexpr int kSetPer = 1024 / kBlock;              // set entries per thread (TSLT_MAX_K_CAP / kBlock)
 
 constexpr int kRowBadSet = 8;      // TSLT_ROW_BAD_SET
@@ -43,9 +48,9 @@ struct VerifyShared {
   BlockScratch red;
   double bcast_d[4];
   int bcast_i[4];
-  double piece_val[kBlock];        // level 1: mass of every piece (n_pieces <= kBlock)
-  double sub_val[kSubChunks];      // level 2: mass of every run of the chosen segment
 };
+constexpr int kMaxPieces = kBlock;                                 // segments of a row that is sampled, plus its two edges
+constexpr int kMaxItems = (kMaxPieces - 2) * kSubChunks + 2;       // its runs, plus the two edges
 
 // A table of exp(s), s = fl32(z / T), for every 16-bit logit z of a magnitude range that holds the bulk of
 // a row: the fp64 sums over the row then cost one LDS read per element instead of an fp64 exponential.
@@ -106,49 +111,64 @@ template <typename T> __device__ __forceinline__ void build_exp_table(double* ta
 
 // Sum of exp(s) over the 8 elements of a 16-bit vector through the table.  The index arithmetic runs on
 // both halves of a 32-bit word at once (16-bit lanes: rotate, saturating subtract, minimum).  An element
-// outside the table's domain reads a NaN entry, which shows in the sum; the vector is then redone
-// element by element.
+// outside the table's domain reads a NaN entry, which shows in the sum: table_vec_sum_raw returns that NaN
+// (so that a caller can add several vectors up and look once), table_vec_redo evaluates a vector element by
+// element, and table_vec_sum is the two together.
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 template <typename T>
-__device__ __forceinline__ double table_vec_sum(const uint4& d, const double* table, float rT, int& flags) {
+__device__ __forceinline__ double table_vec_sum_raw(const uint4& d, const double* table) {
   using TB = ExpTab<T>;
   const uint32_t w[4] = {d.x, d.y, d.z, d.w};
   const ushort2_t base = {uint16_t(2 * TB::kLo - 1), uint16_t(2 * TB::kLo - 1)};
   const ushort2_t top = {uint16_t(TB::kEntries + 1), uint16_t(TB::kEntries + 1)};
+  const ushort2_t one = {1, 1}, fifteen = {15, 15};
   double s0 = 0.0, s1 = 0.0;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
-    const uint32_t rot = ((w[k] << 1) & 0xFFFEFFFEu) | ((w[k] >> 15) & 0x00010001u);
-    ushort2_t i2 = __builtin_elementwise_sub_sat(__builtin_bit_cast(ushort2_t, rot), base);
+    const ushort2_t x = __builtin_bit_cast(ushort2_t, w[k]);
+    const ushort2_t rot = (x << one) | (x >> fifteen);            // sign into bit 0 of each half
+    ushort2_t i2 = __builtin_elementwise_sub_sat(rot, base);
     i2 = __builtin_elementwise_min(i2, top);
     if constexpr (TB::kBytes <= 65536) {      // byte offsets fit the 16-bit lanes
       const ushort2_t three = {3, 3};
       const uint32_t off = __builtin_bit_cast(uint32_t, i2 << three);
       const char* tb = reinterpret_cast<const char*>(table);
-      s0 += *reinterpret_cast<const double*>(tb + (off & 0xFFFFu));
-      s1 += *reinterpret_cast<const double*>(tb + (off >> 16));
+      const double t0 = *reinterpret_cast<const double*>(tb + (off & 0xFFFFu));
+      const double t1 = *reinterpret_cast<const double*>(tb + (off >> 16));
+      s0 = k == 0 ? t0 : s0 + t0;
+      s1 = k == 0 ? t1 : s1 + t1;
     } else {
       const uint32_t ix = __builtin_bit_cast(uint32_t, i2);
-      s0 += table[ix & 0xFFFFu];
-      s1 += table[ix >> 16];
+      const double t0 = table[ix & 0xFFFFu], t1 = table[ix >> 16];
+      s0 = k == 0 ? t0 : s0 + t0;
+      s1 = k == 0 ? t1 : s1 + t1;
     }
   }
-  double s = s0 + s1;
-  if (s != s) {
-    // every element of this lane's vector directly; branch-free, so that a wave in which some lane comes
-    // here for every vector (a row with many values outside the table) runs at the pace of the direct
-    // path and not at that of a divergent loop.  flags: 1 = NaN or +inf, 2 = |s| beyond kTabMaxS
-    s = 0.0;
+  return s0 + s1;
+}
+// Every element of a vector directly; branch-free, so that a wave in which some lane comes here for every
+// vector (a row with many values outside the table) runs at the pace of the direct path and not at that of
+// a divergent loop.  flags: 1 = NaN or +inf, 2 = |s| beyond kTabMaxS
+template <typename T>
+__device__ __forceinline__ double table_vec_redo(const uint4& d, float rT, int& flags) {
+  using TB = ExpTab<T>;
+  const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+  double s = 0.0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint32_t b = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-      const float sv = __fmul_rn(TB::widen(b), rT);
-      const bool neg_inf = b == (0x8000u | TB::kInf);
-      flags |= ((b & 0x7FFFu) > TB::kInf || b == TB::kInf) ? 1 : 0;
-      flags |= (!neg_inf && fabsf(sv) > kTabMaxS) ? 2 : 0;
-      s += exp64(double(sv));                                       // -inf gives exactly 0
-    }
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t b = (w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
+    const float sv = __fmul_rn(TB::widen(b), rT);
+    const bool neg_inf = b == (0x8000u | TB::kInf);
+    flags |= ((b & 0x7FFFu) > TB::kInf || b == TB::kInf) ? 1 : 0;
+    flags |= (!neg_inf && fabsf(sv) > kTabMaxS) ? 2 : 0;
+    s += exp64(double(sv));                                       // -inf gives exactly 0
   }
+  return s;
+}
+template <typename T>
+__device__ __forceinline__ double table_vec_sum(const uint4& d, const double* table, float rT, int& flags) {
+  double s = table_vec_sum_raw<T>(d, table);
+  if (s != s) s = table_vec_redo<T>(d, rT, flags);
   return s;
 }
 
@@ -179,7 +199,7 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
   const int64_t n_tiles = (rs.nvec + kBlock - 1) / kBlock;
   // The pass keeps kAccDepth batches of U vectors in flight per thread; the first ones are requested
   // before anything else, so that they travel while the reference is looked up.
-  constexpr int U = 4;
+  constexpr int U = kAccVecs;
   const uint32_t n_full = uint32_t(rs.nvec / (U * kBlock));      // batches of U complete tiles
   uint4 pipe[kAccDepth][U];
   // Every request of the pipeline is unconditional: a vector past the row's end is read from the row's
@@ -339,15 +359,6 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
     p_s[k] = ok ? p_s[k] / Z : 0.0;
     q_s[k] = sum_w > 0.0 ? q_s[k] / sum_w : 0.0;
   }
-}
-
-// Piece index (0 head edge, 1..n body segments, n+1 tail edge) that holds element y of the row.
-template <typename T> __device__ __forceinline__ int piece_of(const RowSplit& rs, int n_seg_row, int64_t y) {
-  constexpr int E = ElemTraits<T>::kPerVec;
-  if (y < rs.head) return 0;
-  const int64_t v = (y - rs.head) / E;
-  if (v >= rs.nvec) return n_seg_row + 1;
-  return 1 + int(v / kSegVecsTotal);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -513,6 +524,9 @@ struct FinishArgs {
                             //   renormalised.  Null: the same q_hat at every update
   float u;
   int unusable;             // the row is known to be unusable: no token
+  double* item_val;         // LDS scratch of the caller, kMaxItems doubles
+  const double* table;      // the exp table in LDS if the row's run sums were made through it (then every
+                            // piece is referenced to 0), else null
 };
 
 // The set's entries as finish_core needs them, one slot per (thread, k): token index (-1 if unused or out
@@ -541,49 +555,78 @@ __device__ __forceinline__ void load_set_entries(const void* row, int64_t V, con
   }
 }
 
+// Three sums over the workgroup with one pair of barriers.
+template <int NW>
+__device__ __forceinline__ void block_sum3_f64(double& a, double& b, double& c, BlockScratch& s) {
+  a = wave_sum_f64(a); b = wave_sum_f64(b); c = wave_sum_f64(c);
+  __syncthreads();
+  if (lane_id() == 0) { s.d[wave_id()] = a; s.d[4 + wave_id()] = b; s.d[8 + wave_id()] = c; }
+  __syncthreads();
+  a = 0.0; b = 0.0; c = 0.0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) { a += s.d[w]; b += s.d[4 + w]; c += s.d[8 + w]; }
+}
+
 // Returns the token (-1 if none) and ORs TSLT_ROW_* bits into st.  After m updates with the same q_hat
 // the distribution is c * p outside the set and a_i on it, where a and c follow the recursion
 // a <- max(0, a - q_hat) / Z, c <- c / Z, Z = sum(max(0, a - q_hat)) + c * p_out; in units of the row's
 // unnormalised terms e_y that is e_y outside the set and a_i * z_p / c on it.
+//
+// The search runs over "items" in row order: the head edge, every run of the body, the tail edge.  Every
+// thread lays out its share of the item masses in LDS, the set's corrections are added to the items they
+// fall into, and then every wave finds the item at which the cumulative mass passes the target by itself (a
+// scan over the wave, the same in all of them), so that nothing has to be handed round; the element inside
+// the chosen run is found from one vector per thread.  Called by all kBlock threads of a workgroup.
 template <typename T>
 __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const SetEntries* pre = nullptr) {
+  static_assert(kWaves == 4, "block_sum3_f64 lays its partial sums out for four waves");
   constexpr int E = ElemTraits<T>::kPerVec;
   constexpr int kMaxPer = kSetPer;
   constexpr int kRun = kRunVecs * E;        // elements in a run
-  constexpr int kPerT = kRun / kBlock;      // consecutive elements per thread at level 3 (one vector)
-  __shared__ double elem_corr[kRunVecs * 8];   // level 3: sparse correction per element of the chosen run
+  constexpr int kPerT = kRun / kBlock;      // consecutive elements per thread in the chosen run (one vector)
+  __shared__ double elem_corr[kRunVecs * 8];   // sparse correction per element of the chosen run
+  double* item_val = a.item_val;               // mass of every item
   const int tid = threadIdx.x;
+  const int lane = lane_id();
   const RowSplit& rs = a.rs;
   const void* row = a.row;
   const int n_seg_row = a.n_seg_row;
   const int n_pieces = n_seg_row + 2;
+  const int n_runs = n_seg_row * kSubChunks;       // runs past the row's end hold no mass
+  const int n_items = n_runs + 2;
   const SegResult* segs = a.segs;
   const int broken_flag = a.unusable;
   const float rT = a.rT;
-  // maximum and validity of the row, from the pieces
+  for (int i = tid; i < kRun; i += kBlock) elem_corr[i] = 0.0;      // published by the first barrier below
+  // maximum and validity of the row, from the pieces; every wave looks at all of them
   float smax = -INFINITY;
   int bad = 0;
   if (!broken_flag)
-    for (int k = tid; k < n_pieces; k += kBlock) { smax = fmaxf(smax, segs[k].smax); bad |= segs[k].bad; }
-  smax = block_max_f32<kWaves>(smax, sh.red);
-  bad = __syncthreads_or(bad);
+    for (int k = lane; k < n_pieces; k += 64) { smax = fmaxf(smax, segs[k].smax); bad |= segs[k].bad; }
+  smax = wave_max_f32(smax);
+  bad = wave_or_i32(bad);
   int token = -1;
   const bool usable = !broken_flag && !bad && smax > -INFINITY;
   if (!broken_flag && bad) st |= 1;
   if (!broken_flag && !bad && !(smax > -INFINITY)) st |= 2;
 
   if (usable) {
-    // unnormalised target mass of every piece, referenced to the row maximum, and their total z_p
+    // unnormalised target mass of every item, referenced to the row maximum, and their total z_p
     double zp = 0.0;
-    for (int k = tid; k < n_pieces; k += kBlock) {
-      const double t = segs[k].smax > -INFINITY ? segs[k].sum * exp64(double(segs[k].smax) - double(smax)) : 0.0;
-      sh.piece_val[k] = t;
+    for (int it = tid; it < n_items; it += kBlock) {
+      double t;
+      if (it == 0 || it == n_items - 1) {
+        const SegResult& e = segs[it == 0 ? 0 : n_pieces - 1];
+        t = e.smax > -INFINITY ? e.sum * exp64(double(e.smax) - double(smax)) : 0.0;
+      } else {
+        const float m = segs[1 + (it - 1) / kSubChunks].smax;
+        t = m > -INFINITY ? a.subs[it - 1] * exp64(double(m) - double(smax)) : 0.0;
+      }
+      item_val[it] = t;
       zp += t;
     }
-    zp = block_sum_f64<kWaves>(zp, sh.red);
 
-    // sparse corrections at the set's indices: after `stages` residual updates the mass of entry i is
-    // a_i * z_p / c instead of e_i
+    // the set: after `stages` residual updates the mass of entry i is a_i * z_p / c instead of e_i
     const int stages = a.stages;
     int count = stages > 0 ? a.count : 0;
     SetEntries se_local;
@@ -593,11 +636,12 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const
     double w64[kMaxPer], corr[kMaxPer], e_s[kMaxPer];
     int yi[kMaxPer];
     double sum_w = 0.0, sum_e = 0.0;
+    const int n_slots = (count + kBlock - 1) / kBlock;      // slots of a thread that can hold an entry
 #pragma unroll
     for (int k = 0; k < kMaxPer; ++k) {
       const int i = tid + k * kBlock;
       w64[k] = 0.0; corr[k] = 0.0; e_s[k] = 0.0; yi[k] = -1;
-      if (i < count) {
+      if (k < n_slots && i < count) {
         w64[k] = exp64(double(se.ql[k]) - ql0);
         sum_w += w64[k];
         if (se.yi[k] >= 0) {
@@ -608,15 +652,19 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const
         }
       }
     }
-    sum_w = block_sum_f64<kWaves>(sum_w, sh.red);
-    sum_e = block_sum_f64<kWaves>(sum_e, sh.red);
+    block_sum3_f64<kWaves>(zp, sum_w, sum_e, sh.red);
     double sum_corr = 0.0;
     if (count > 0) {
       double av[kMaxPer];
+      const double inv_zp = 1.0 / zp, inv_w = 1.0 / sum_w;
 #pragma unroll
-      for (int k = 0; k < kMaxPer; ++k) { av[k] = e_s[k] / zp; w64[k] = w64[k] / sum_w; }
-      const double p_out = 1.0 - sum_e / zp;
+      for (int k = 0; k < kMaxPer; ++k) {
+        av[k] = 0.0;
+        if (k < n_slots) { av[k] = e_s[k] * inv_zp; w64[k] = w64[k] * inv_w; }
+      }
+      const double p_out = 1.0 - sum_e * inv_zp;
       double c = 1.0;
+      double sum_av = sum_e / zp;               // sum of av over the set, kept up to date through the updates
       const int32_t* cands = a.cands;
       int ci = 0;
       double qscale = 1.0, removed = 0.0;       // the update's proposal is w64 * qscale
@@ -624,15 +672,21 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const
         double part = 0.0;
 #pragma unroll
         for (int k = 0; k < kMaxPer; ++k) {
-          const double d = av[k] - w64[k] * qscale;
-          av[k] = (yi[k] >= 0 && d > 0.0) ? d : 0.0;
-          part += av[k];
+          if (k < n_slots) {
+            const double d = av[k] - w64[k] * qscale;
+            av[k] = (yi[k] >= 0 && d > 0.0) ? d : 0.0;
+            part += av[k];
+          }
         }
-        const double Zs = block_sum_f64<kWaves>(part, sh.red) + c * (p_out > 0.0 ? p_out : 0.0);
+        part = block_sum_f64<kWaves>(part, sh.red);
+        const double Zs = part + c * (p_out > 0.0 ? p_out : 0.0);
+        sum_av = part;
         if (Zs > 0.0) {
+          const double inv_Zs = 1.0 / Zs;
 #pragma unroll
-          for (int k = 0; k < kMaxPer; ++k) av[k] /= Zs;
-          c /= Zs;
+          for (int k = 0; k < kMaxPer; ++k) av[k] *= inv_Zs;
+          c *= inv_Zs;
+          sum_av = part * inv_Zs;
         }
         if (cands != nullptr) {
           // the candidate that this update rejected leaves the urn
@@ -650,15 +704,12 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const
           qscale = rest > 0.0 ? 1.0 / rest : 0.0;
         }
       }
+      const double zp_over_c = zp / c;
 #pragma unroll
-      for (int k = 0; k < kMaxPer; ++k) {
-        if (yi[k] >= 0) {
-          corr[k] = av[k] * zp / c - e_s[k];
-          sum_corr += corr[k];
-        }
-      }
+      for (int k = 0; k < kMaxPer; ++k)
+        if (yi[k] >= 0) corr[k] = av[k] * zp_over_c - e_s[k];
+      sum_corr = sum_av * zp_over_c - sum_e;    // the sum of the corrections, without another pass over the workgroup
     }
-    sum_corr = block_sum_f64<kWaves>(sum_corr, sh.red);
     double total = zp + sum_corr;
     bool use_corr = true;
     if (!(total > 0.0)) {          // defensive: an all-zero residual falls back to p itself
@@ -669,48 +720,63 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const
     }
     const double target = double(a.u) * total;
 
-    // ---- level 1: which piece ---------------------------------------------------------------------
+    // ---- which item: corrections into the items they fall into, then a scan per wave ------------------------
+    auto item_of = [&](int y) {
+      if (y < rs.head) return 0;
+      const int64_t v = (int64_t(y) - rs.head) / E;
+      return v >= rs.nvec ? n_items - 1 : 1 + int(v / kRunVecs);
+    };
 #pragma unroll
     for (int k = 0; k < kMaxPer; ++k)
-      if (yi[k] >= 0 && corr[k] != 0.0) atomicAdd(&sh.piece_val[piece_of<T>(rs, n_seg_row, yi[k])], corr[k]);
+      if (yi[k] >= 0 && corr[k] != 0.0) atomicAdd(&item_val[item_of(yi[k])], corr[k]);
     __syncthreads();
-    if (tid == 0) {
-      double run = 0.0, before = 0.0, last_before = 0.0;
-      int piece = -1, last_pos = -1;
-      for (int k = 0; k < n_pieces; ++k) {
-        const double t = sh.piece_val[k];
-        if (t > 0.0) {
-          last_pos = k; last_before = run;
-          if (run + t > target) { piece = k; before = run; break; }
-          run += t;
-        }
-      }
-      if (piece < 0) { piece = last_pos; before = last_before; }
-      sh.bcast_i[0] = piece;
-      sh.bcast_d[0] = before;
+    const int per = (n_items + 63) / 64;          // consecutive items per lane
+    double lsum = 0.0;
+    for (int q = 0; q < per; ++q) {
+      const int it = lane * per + q;
+      const double t = it < n_items ? item_val[it] : 0.0;
+      lsum += t > 0.0 ? t : 0.0;
     }
-    __syncthreads();
-    const int piece = sh.bcast_i[0];
-    const double before_piece = sh.bcast_d[0];
-    __syncthreads();
-
-    if (piece == 0 || piece == n_pieces - 1) {
-      // an edge piece: fewer than E elements, walked by one thread
-      {
-        const int e0 = piece == 0 ? 0 : rs.head;
-        if (tid < 2 * E) elem_corr[tid] = 0.0;
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < kMaxPer; ++k)
-          if (yi[k] >= 0 && piece_of<T>(rs, n_seg_row, yi[k]) == piece) {
-            const int e = yi[k] < rs.head ? yi[k] : rs.head + int(yi[k] - (rs.head + rs.nvec * E));
-            elem_corr[e - e0] = corr[k];
-          }
-        __syncthreads();
+    double run = wave_incl_scan_f64(lsum) - lsum;
+    int found = -1, last_pos = -1;
+    double found_before = 0.0, last_before = 0.0;
+    for (int q = 0; q < per; ++q) {
+      const int it = lane * per + q;
+      const double t = it < n_items ? item_val[it] : 0.0;
+      if (t > 0.0) {
+        last_pos = it; last_before = run;
+        if (run + t > target && found < 0) { found = it; found_before = run; }
+        run += t;
       }
+    }
+    // the first lane that saw the target passed, else the last one that holds an item with mass
+    const uint64_t hit = ballot(found >= 0), any = ballot(last_pos >= 0);
+    int item = -1;
+    double before_item = 0.0;
+    if (hit != 0) {
+      const int src = __ffsll((long long)hit) - 1;
+      item = __shfl(found, src, 64);
+      before_item = shfl_f64(found_before, src);
+    } else if (any != 0) {
+      const int src = 63 - __clzll((long long)any);
+      item = __shfl(last_pos, src, 64);
+      before_item = shfl_f64(last_before, src);
+    }
+
+    if (item == 0 || item == n_items - 1) {
+      // an edge piece: fewer than E elements, walked by one thread
+      const int piece = item == 0 ? 0 : n_pieces - 1;
+      const int e0 = piece == 0 ? 0 : rs.head;
+#pragma unroll
+      for (int k = 0; k < kMaxPer; ++k)
+        if (yi[k] >= 0 && item_of(yi[k]) == item) {
+          const int e = yi[k] < rs.head ? yi[k] : rs.head + int(yi[k] - (rs.head + rs.nvec * E));
+          elem_corr[e - e0] = corr[k];
+        }
+      __syncthreads();
       if (tid == 0) {
-        const int e0 = piece == 0 ? 0 : rs.head, e1 = piece == 0 ? rs.head : rs.head + rs.tail;
-        double run = before_piece;
+        const int e1 = piece == 0 ? rs.head : rs.head + rs.tail;
+        double run_e = before_item;
         for (int e = e0; e < e1; ++e) {
           const int64_t y = edge_index<T>(rs, e);
           const float t = load_elem<T>(row, y);
@@ -721,100 +787,80 @@ __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const
           }
           if (v > 0.0) {
             token = int(y);
-            run += v;
-            if (run > target) break;
+            run_e += v;
+            if (run_e > target) break;
           }
         }
         sh.bcast_i[3] = token;
       }
       __syncthreads();
       token = sh.bcast_i[3];
-    } else if (piece > 0) {
-      // ---- level 2: which run of the body segment ------------------------
-      const int seg = piece - 1;
-      const int64_t seg_first_vec = int64_t(seg) * kSegVecsTotal;
-      const int64_t seg_first_elem = rs.head + seg_first_vec * E;
-      const double seg_scale = exp64(double(segs[piece].smax) - double(smax));
-      const double* subs = a.subs + size_t(seg) * kSubChunks;
-      if (tid < kSubChunks) sh.sub_val[tid] = subs[tid] * seg_scale;
-      __syncthreads();
+    } else if (item > 0) {
+      // ---- which element of that run; thread t owns kPerT consecutive elements: one vector, requested
+      // before the corrections are laid out, so that it travels meanwhile ------------------------------------
+      static_assert(kPerT == E, "a thread's share of a run is one vector");
+      const int r = item - 1;
+      const int64_t run_first = rs.head + int64_t(r) * kRun;
+      const int64_t my_vec = int64_t(r) * kRunVecs + tid;
+      uint4 dv = neg_inf_vec<T>();
+      if (my_vec < rs.nvec) dv = load_vec(&rs.body[my_vec]);
 #pragma unroll
       for (int k = 0; k < kMaxPer; ++k)
-        if (yi[k] >= 0 && corr[k] != 0.0 && piece_of<T>(rs, n_seg_row, yi[k]) == piece)
-          atomicAdd(&sh.sub_val[(yi[k] - seg_first_elem) / kRun], corr[k]);
+        if (yi[k] >= run_first && yi[k] < run_first + kRun) elem_corr[yi[k] - run_first] = corr[k];
       __syncthreads();
-      if (tid == 0) {
-        double run = before_piece, before = before_piece, last_before = before_piece;
-        int sub = -1, last_pos = -1;
-        for (int c = 0; c < kSubChunks; ++c) {
-          const double t = sh.sub_val[c];
-          if (t > 0.0) {
-            last_pos = c; last_before = run;
-            if (run + t > target) { sub = c; before = run; break; }
-            run += t;
+      float tv[E];
+      unpack<T>(dv, tv);
+      double v[kPerT];
+      double mine = 0.0;
+      // the terms as the sweep made them: through the table where it was used (then smax is 0 and an entry is
+      // the term itself), else the exponential
+      bool by_table = false;
+      if constexpr (ExpTab<T>::kHas) by_table = a.table != nullptr && smax == 0.0f;
+#pragma unroll
+      for (int q = 0; q < kPerT; ++q) {
+        v[q] = 0.0;
+        if (my_vec < rs.nvec) {
+          double term = __longlong_as_double(0x7FF8000000000000ll);
+          if constexpr (ExpTab<T>::kHas) {
+            if (by_table) {
+              const uint32_t w4[4] = {dv.x, dv.y, dv.z, dv.w};
+              const uint32_t bits = (w4[q >> 1] >> ((q & 1) * 16)) & 0xFFFFu;
+              const int rot = int(((bits << 1) & 0xFFFEu) | (bits >> 15)) - (2 * ExpTab<T>::kLo - 1);
+              term = a.table[rot < 0 ? 0 : (rot > ExpTab<T>::kEntries + 1 ? ExpTab<T>::kEntries + 1 : rot)];
+            }
           }
+          if (term != term) term = exp64(double(__fmul_rn(tv[q], rT)) - double(smax));
+          v[q] = term + elem_corr[tid * kPerT + q];
+          if (v[q] < 0.0) v[q] = 0.0;
         }
-        if (sub < 0) { sub = last_pos; before = last_before; }
-        sh.bcast_i[1] = sub;
-        sh.bcast_d[1] = before;
+        mine += v[q];
       }
-      for (int i = tid; i < kRun; i += kBlock) elem_corr[i] = 0.0;
+      double run_total;
+      const double excl = block_excl_scan_f64<kWaves>(mine, sh.red, run_total);
+      // element at which the cumulative mass passes the target, else the last one with mass
+      int first_pass = 0x7FFFFFFF, last_mass = -1;
+      double run_e = before_item + excl;
+#pragma unroll
+      for (int q = 0; q < kPerT; ++q) {
+        if (v[q] > 0.0) {
+          run_e += v[q];
+          last_mass = tid * kPerT + q;
+          if (run_e > target && first_pass == 0x7FFFFFFF) first_pass = tid * kPerT + q;
+        }
+      }
+      first_pass = -wave_max_i32(-first_pass);      // the smallest over the wave (0x7FFFFFFF = none)
+      last_mass = wave_max_i32(last_mass);
       __syncthreads();
-      const int sub = sh.bcast_i[1];
-      const double before_run = sh.bcast_d[1];
-      if (sub >= 0) {
-        // ---- level 3: which element of that run; thread t owns kPerT consecutive elements ------------
-        const int64_t run_first = seg_first_elem + int64_t(sub) * kRun;
-        // a thread's kPerT elements are one vector of the run; it is requested before the corrections are
-        // laid out, so that it travels meanwhile
-        static_assert(kPerT == E, "a thread's share of a run is one vector");
-        const int64_t my_vec = seg_first_vec + int64_t(sub) * kRunVecs + tid;
-        uint4 dv = neg_inf_vec<T>();
-        if (my_vec < rs.nvec) dv = load_vec(&rs.body[my_vec]);
+      if (lane == 0) { sh.red.i[wave_id()] = first_pass; sh.red.i[8 + wave_id()] = last_mass; }
+      __syncthreads();
+      first_pass = 0x7FFFFFFF; last_mass = -1;
 #pragma unroll
-        for (int k = 0; k < kMaxPer; ++k)
-          if (yi[k] >= run_first && yi[k] < run_first + kRun) elem_corr[yi[k] - run_first] = corr[k];
-        __syncthreads();
-        float tv[E];
-        unpack<T>(dv, tv);
-        double v[kPerT];
-        double mine = 0.0;
-#pragma unroll
-        for (int q = 0; q < kPerT; ++q) {
-          v[q] = 0.0;
-          if (my_vec < rs.nvec) {
-            v[q] = exp64(double(__fmul_rn(tv[q], rT)) - double(smax)) + elem_corr[tid * kPerT + q];
-            if (v[q] < 0.0) v[q] = 0.0;
-          }
-          mine += v[q];
-        }
-        double run_total;
-        const double excl = block_excl_scan_f64<kWaves>(mine, sh.red, run_total);
-        // element at which the cumulative mass passes the target, else the last one with mass
-        int first_pass = 0x7FFFFFFF, last_mass = -1;
-        double run = before_run + excl;
-#pragma unroll
-        for (int q = 0; q < kPerT; ++q) {
-          if (v[q] > 0.0) {
-            run += v[q];
-            last_mass = tid * kPerT + q;
-            if (run > target && first_pass == 0x7FFFFFFF) first_pass = tid * kPerT + q;
-          }
-        }
-        first_pass = -wave_max_i32(-first_pass);      // the smallest over the wave (0x7FFFFFFF = none)
-        last_mass = wave_max_i32(last_mass);
-        __syncthreads();
-        if (lane_id() == 0) { sh.red.i[wave_id()] = first_pass; sh.red.i[8 + wave_id()] = last_mass; }
-        __syncthreads();
-        first_pass = 0x7FFFFFFF; last_mass = -1;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-          first_pass = sh.red.i[w] < first_pass ? sh.red.i[w] : first_pass;
-          last_mass = sh.red.i[8 + w] > last_mass ? sh.red.i[8 + w] : last_mass;
-        }
-        const int pick = first_pass != 0x7FFFFFFF ? first_pass : last_mass;
-        token = pick >= 0 ? int(run_first + pick) : -1;
+      for (int w = 0; w < kWaves; ++w) {
+        first_pass = sh.red.i[w] < first_pass ? sh.red.i[w] : first_pass;
+        last_mass = sh.red.i[8 + w] > last_mass ? sh.red.i[8 + w] : last_mass;
       }
+      const int pick = first_pass != 0x7FFFFFFF ? first_pass : last_mass;
+      token = pick >= 0 ? int(run_first + pick) : -1;
     }
   }
   return token;

@@ -27,7 +27,7 @@ struct StatsParams {
 // One workgroup per row: the pass of the acceptance kernel (normaliser of the target row, p and q_hat at
 // the set's entries), then per K two block sums over the prefix.
 template <typename T>
-__global__ __launch_bounds__(kBlock) void truncation_stats_kernel(const StatsParams p) {
+__global__ __launch_bounds__(kBlock, kAccWavesPerSimd) void truncation_stats_kernel(const StatsParams p) {
   __shared__ VerifyShared sh;
   const int tid = threadIdx.x;
   const int64_t r = blockIdx.x;
@@ -87,7 +87,7 @@ struct McStatsParams {
 };
 
 template <typename T>
-__global__ __launch_bounds__(kBlock) void multicandidate_stats_kernel(const McStatsParams p) {
+__global__ __launch_bounds__(kBlock, kAccWavesPerSimd) void multicandidate_stats_kernel(const McStatsParams p) {
   __shared__ VerifyShared sh;
   const int tid = threadIdx.x;
   const int64_t r = blockIdx.x;

@@ -196,7 +196,7 @@ __device__ __forceinline__ int mcveri_node(const TreeParams& p, int64_t b, int n
 }
 
 template <typename T>
-__global__ __launch_bounds__(kBlock) void tree_mcveri_kernel(const TreeParams p) {
+__global__ __launch_bounds__(kBlock, kAccWavesPerSimd) void tree_mcveri_kernel(const TreeParams p) {
   __shared__ VerifyShared sh;
   const int64_t b = blockIdx.x / p.n_int;
   const int node = int(blockIdx.x - b * p.n_int);
@@ -302,6 +302,7 @@ __global__ __launch_bounds__(kBlock) void tree_sweep_kernel(const TreeParams p) 
 template <typename T>
 __global__ __launch_bounds__(kBlock) void tree_finish_kernel(const TreeParams p) {
   __shared__ VerifyShared sh;
+  __shared__ double item_val[kMaxItems];
   const int tid = threadIdx.x;
   const int64_t task = blockIdx.x;
   const int64_t b = task / p.tasks;
@@ -338,6 +339,8 @@ __global__ __launch_bounds__(kBlock) void tree_finish_kernel(const TreeParams p)
     }
     a.u = p.u_resample[size_t(b) * p.n_nodes + node];
     a.unusable = state == 2;
+    a.item_val = item_val;
+    a.table = nullptr;
     token = finish_core<T>(a, sh, st);
   }
   if (tid == 0) {

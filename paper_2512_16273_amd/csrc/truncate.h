@@ -20,8 +20,10 @@
 namespace tslt {
 
 constexpr int kTruncThreads = 256;   // threads of a truncate workgroup (one row each)
-constexpr int kBatch = 4;        // tiles per batch; the first batch is the threshold sample
-constexpr int kDepth = 2;        // batches in flight per thread during the pass
+constexpr int kBatch = 4;        // tiles of the threshold sample, taken at equal distances over the row
+constexpr int kGroup = 2;        // tiles (one 16-byte vector per thread each) in a stage of the pass's pipeline
+constexpr int kStages = 2;       // stages in flight per thread during the pass
+constexpr int kTruncWavesPerSimd = 8;   // asked of the compiler: 64 registers, eight workgroups per compute unit
 constexpr int kRing = 96;      // vectors a wave can park
 constexpr int kRingExpand = 58; // expanded when it holds more than this: one pass of 64 lanes, nearly all busy
 
@@ -362,10 +364,10 @@ template <> __device__ __forceinline__ float vec_max<Bf16>(const float (&v)[8]) 
 template <> __device__ __forceinline__ float vec_max<F16>(const float (&v)[8]) { return vec_max8(v); }
 
 template <typename T, int NT>
-__global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
+__global__ __launch_bounds__(NT, kTruncWavesPerSimd) void truncate_kernel(const TruncateParams p) {
   constexpr int E = ElemTraits<T>::kPerVec;
   constexpr int NW = NT / 64;
-  static_assert(kBatch == 4, "the pass handles a batch as two pairs of tiles");
+  static_assert(kBatch == 4, "the sample tiles are handled as two pairs");
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ TruncateShared sh;
   uint4* ring_all = reinterpret_cast<uint4*>(dyn_lds);
@@ -420,28 +422,28 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
     // ---- the sample: per-thread maxima ----------------------------------------------------------
     uint4 d[kBatch];
     load_sample(rs, d);
-    // The pass keeps kDepth batches in flight per thread; the first ones are requested now, so that they
-    // travel while the threshold is being worked out.  The first tile of a sample batch is not read again.
-    // A long row's ragged end (fewer than kBatch tiles, the last one possibly incomplete) is one more batch.
-    uint4 pipe[kDepth][kBatch];
-    const uint32_t n_pipe = long_row ? n_full + (n_tiles > n_full * kBatch ? 1u : 0u) : 0u;
-    uint32_t skip_b = 0, skips_left = kBatch;
-    const uint32_t stride_b = s_stride / kBatch;
+    // The pass keeps kStages stages of kGroup tiles in flight per thread; the first ones are requested now, so
+    // that they travel while the threshold is being worked out.  A sample tile is the first tile of its stage
+    // (the sample tiles lie a multiple of kBatch tiles apart) and is not read again.  A long row's ragged end
+    // (the last tile possibly incomplete, the last stage possibly half empty) is the last stage.
+    static_assert(kBatch % kGroup == 0 && kGroup == 2, "a stage is a pair of tiles; sample tiles start a stage");
+    uint4 pipe[kStages][kGroup];
+    const uint32_t n_stage = long_row ? (n_tiles + kGroup - 1) / kGroup : 0u;
+    uint32_t skip_g = 0, skips_left = kBatch;
+    const uint32_t stride_g = s_stride / kGroup;
     const uint32_t last_vec = nvec - 1;
-    auto issue = [&](uint32_t b, uint4 (&q)[kBatch]) {
-      const uint32_t v0 = b * (kBatch * NT) + tid;
-      // the first tile of a sample batch is in registers already: its slot repeats the second tile's load
-      const bool skip = skips_left > 0 && b == skip_b;
-      if (skip) { skip_b += stride_b; --skips_left; }
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const uint32_t vi = v0 + ((u == 0 && skip) ? 1 : u) * NT;
-        q[u] = load_vec_stream(&rs.body[vi < last_vec ? vi : last_vec]);
-      }
+    auto issue = [&](uint32_t g, uint4 (&q)[kGroup]) {
+      const uint32_t v0 = g * (kGroup * NT) + tid;
+      // the first tile of a sample stage is in registers already: its slot repeats the second tile's load
+      const bool skip = skips_left > 0 && g == skip_g;
+      if (skip) { skip_g += stride_g; --skips_left; }
+      const uint32_t va = skip ? v0 + NT : v0, vb = v0 + NT;
+      q[0] = load_vec_stream(&rs.body[va < last_vec ? va : last_vec]);
+      q[1] = load_vec_stream(&rs.body[vb < last_vec ? vb : last_vec]);
     };
-    if (n_pipe > 0) {
+    if (n_stage > 0) {
 #pragma unroll
-      for (int s = 0; s < kDepth; ++s) issue(uint32_t(s), pipe[s]);
+      for (int s = 0; s < kStages; ++s) issue(uint32_t(s), pipe[s]);
     }
     float tmax = -INFINITY;
 #pragma unroll
@@ -450,6 +452,10 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
       unpack<T>(d[u], v);
       tmax = fmaxf(tmax, vec_max<T>(v));
     }
+    // the sample is looked at again after the threshold is known; it is to wait in its packed form (the
+    // compiler would otherwise keep the unpacked values, twice the registers, across the threshold search)
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) asm volatile("" : "+v"(d[u].x), "+v"(d[u].y), "+v"(d[u].z), "+v"(d[u].w));
     tables[tid] = mono_key(tmax);
     __syncthreads();
     // ---- tau0: the jprime-th largest of the 256 per-thread sample maxima (every wave redundantly)
@@ -542,28 +548,26 @@ __global__ __launch_bounds__(NT) void truncate_kernel(const TruncateParams p) {
       }
       uint32_t first_generic_tile = kBatch;             // short rows: everything after the sample tiles
       if (long_row) {
-        // complete batches
-        uint32_t seen_b = 0, seen_left = kBatch;
-        for (uint32_t b = 0; b < n_pipe; b += kDepth) {
+        uint32_t seen_g = 0, seen_left = kBatch;
+        const uint32_t ragged_g = n_full * (kBatch / kGroup);        // from here on a vector may lie past the row's end
+        for (uint32_t g0 = 0; g0 < n_stage; g0 += kStages) {
 #pragma unroll
-          for (int s = 0; s < kDepth; ++s) {
-            const uint32_t bb = b + s;
-            if (bb < n_pipe) {                                      // wave-uniform, no loads inside
-              const uint32_t v0 = bb * (kBatch * NT) + tid;
-              if (seen_left > 0 && bb == seen_b) {                  // a sample batch: its first tile is done
-                seen_b += stride_b; --seen_left;
+          for (int s = 0; s < kStages; ++s) {
+            const uint32_t g = g0 + s;
+            if (g < n_stage) {                                        // wave-uniform, no loads inside
+              const uint32_t v0 = g * (kGroup * NT) + tid;
+              if (seen_left > 0 && g == seen_g) {                     // a sample stage: its first tile is done
+                seen_g += stride_g; --seen_left;
                 pipe[s][0] = neg_inf_vec<T>();
               }
-              if (bb >= n_full) {                                   // the ragged end
-#pragma unroll
-                for (int u = 0; u < kBatch; ++u)
-                  if (v0 + u * NT >= nvec) pipe[s][u] = neg_inf_vec<T>();
+              if (g >= ragged_g) {                                    // the ragged end
+                if (v0 >= nvec) pipe[s][0] = neg_inf_vec<T>();
+                if (v0 + NT >= nvec) pipe[s][1] = neg_inf_vec<T>();
               }
               process_pair(pipe[s][0], pipe[s][1], v0, v0 + NT);
-              process_pair(pipe[s][2], pipe[s][3], v0 + 2 * NT, v0 + 3 * NT);
               flush();
             }
-            issue(bb + kDepth, pipe[s]);
+            issue(g + kStages, pipe[s]);
           }
         }
         first_generic_tile = n_tiles;
