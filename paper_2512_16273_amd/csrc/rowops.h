@@ -104,9 +104,14 @@ template <typename T> __device__ __forceinline__ double exp_table_entry(int i, f
   const uint32_t bits = (uint32_t(j & 1) << 15) | uint32_t(TB::kLo + (j >> 1));
   return exp64(double(__fmul_rn(TB::widen(bits), rT)));
 }
-// Fills the table with all `threads` threads of the workgroup; the caller synchronises.
-template <typename T> __device__ __forceinline__ void build_exp_table(double* table, float rT, int threads) {
-  for (int i = threadIdx.x; i < ExpTab<T>::kEntries + 2; i += threads) table[i] = exp_table_entry<T>(i, rT);
+// Fills the table with all `threads` threads of the workgroup; the caller synchronises.  `half` 0 / 1 fills the
+// first / second half only (a kernel that has requests to make between the two does so: the entries are
+// pure arithmetic, a good thing to have while data travels), -1 everything.
+template <typename T> __device__ __forceinline__ void build_exp_table(double* table, float rT, int threads, int half = -1) {
+  constexpr int n = ExpTab<T>::kEntries + 2;
+  const int mid = ((n / 2 + threads - 1) / threads) * threads;
+  const int lo = half == 1 ? mid : 0, hi = half == 0 ? mid : n;
+  for (int i = lo + threadIdx.x; i < hi; i += threads) table[i] = exp_table_entry<T>(i, rT);
 }
 
 // Sum of exp(s) over the 8 elements of a 16-bit vector through the table.  The index arithmetic runs on

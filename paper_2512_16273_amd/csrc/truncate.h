@@ -484,14 +484,9 @@ __global__ __launch_bounds__(NT, kTruncWavesPerSimd) void truncate_kernel(const 
       // ---- the pass -------------------------------------------------------------------------
       const float neg_c = -c_ref;
       const float k2 = p.k2;
-      // fp32 sums live for one batch only and are then added to an fp64 total: a long-lived fp32
+      // fp32 sums live for a few vectors only and are then added to an fp64 total: a long-lived fp32
       // accumulator that has met one large term rounds away the many small ones that follow
-      float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
       double dacc = 0.0;
-      auto flush = [&]() {
-        dacc += double((acc0 + acc1) + (acc2 + acc3));
-        acc0 = acc1 = acc2 = acc3 = 0.f;
-      };
       int wave_cnt = 0;                                // pairs parked in this wave's ring
       bool lost = false;                               // wave-uniform: a ring overflowed
       uint4* ring = ring_all + wave * kRing;
@@ -500,25 +495,23 @@ __global__ __launch_bounds__(NT, kTruncWavesPerSimd) void truncate_kernel(const 
 
       // Two vectors at a time: their exp2 terms go to the partial sums; a vector with an element above
       // tau0 is parked in the ring, which is expanded when it holds about a wave's worth of vectors.
-      auto process_pair = [&](const uint4& w0, const uint4& w1, uint32_t vidx0, uint32_t vidx1) {
+      // (returns the sum of the pair's exp2 terms)
+      auto process_pair = [&](const uint4& w0, const uint4& w1, uint32_t vidx0, uint32_t vidx1) -> float {
         float a[E], b[E];
         unpack<T>(w0, a);
         unpack<T>(w1, b);
         const bool hit_a = vec_max<T>(a) > tau0, hit_b = vec_max<T>(b) > tau0;
+        float t[2 * E];
 #pragma unroll
-        for (int e = 0; e < E; e += 4) {
-          acc0 += fast_exp2(__builtin_fmaf(a[e + 0], k2, neg_c));
-          acc1 += fast_exp2(__builtin_fmaf(a[e + 1], k2, neg_c));
-          acc2 += fast_exp2(__builtin_fmaf(a[e + 2], k2, neg_c));
-          acc3 += fast_exp2(__builtin_fmaf(a[e + 3], k2, neg_c));
+        for (int e = 0; e < E; ++e) {
+          t[e] = fast_exp2(__builtin_fmaf(a[e], k2, neg_c));
+          t[E + e] = fast_exp2(__builtin_fmaf(b[e], k2, neg_c));
         }
 #pragma unroll
-        for (int e = 0; e < E; e += 4) {
-          acc0 += fast_exp2(__builtin_fmaf(b[e + 0], k2, neg_c));
-          acc1 += fast_exp2(__builtin_fmaf(b[e + 1], k2, neg_c));
-          acc2 += fast_exp2(__builtin_fmaf(b[e + 2], k2, neg_c));
-          acc3 += fast_exp2(__builtin_fmaf(b[e + 3], k2, neg_c));
-        }
+        for (int w = E; w >= 1; w >>= 1)          // a tree: 2E - 1 additions, none of them with a zero
+#pragma unroll
+          for (int e = 0; e < w; ++e) t[e] += t[e + w];
+        const float pair_sum = t[0];
         const uint64_t mask_a = ballot(hit_a), mask_b = ballot(hit_b);
         if ((mask_a | mask_b) != 0) {
           const int n_a = __popcll(mask_a);
@@ -537,20 +530,23 @@ __global__ __launch_bounds__(NT, kTruncWavesPerSimd) void truncate_kernel(const 
             wave_cnt = 0;
           }
         }
+        return pair_sum;
       };
 
       // the sample tiles, already in registers
       {
         const uint32_t t1 = s_stride, t2 = 2 * s_stride, t3 = 3 * s_stride;
-        process_pair(d[0], d[1], tid, t1 * NT + tid);
-        process_pair(d[2], d[3], t2 * NT + tid, t3 * NT + tid);
-        flush();
+        const float s01 = process_pair(d[0], d[1], tid, t1 * NT + tid);
+        const float s23 = process_pair(d[2], d[3], t2 * NT + tid, t3 * NT + tid);
+        dacc += double(s01 + s23);
       }
       uint32_t first_generic_tile = kBatch;             // short rows: everything after the sample tiles
       if (long_row) {
         uint32_t seen_g = 0, seen_left = kBatch;
         const uint32_t ragged_g = n_full * (kBatch / kGroup);        // from here on a vector may lie past the row's end
+        static_assert(kStages % 2 == 0, "the fp32 sums of two stages are added up before they go to the fp64 total");
         for (uint32_t g0 = 0; g0 < n_stage; g0 += kStages) {
+          float two = 0.0f;
 #pragma unroll
           for (int s = 0; s < kStages; ++s) {
             const uint32_t g = g0 + s;
@@ -564,9 +560,10 @@ __global__ __launch_bounds__(NT, kTruncWavesPerSimd) void truncate_kernel(const 
                 if (v0 >= nvec) pipe[s][0] = neg_inf_vec<T>();
                 if (v0 + NT >= nvec) pipe[s][1] = neg_inf_vec<T>();
               }
-              process_pair(pipe[s][0], pipe[s][1], v0, v0 + NT);
-              flush();
+              const float ps = process_pair(pipe[s][0], pipe[s][1], v0, v0 + NT);
+              two = (s & 1) ? two + ps : ps;
             }
+            if ((s & 1) && g0 + s - 1 < n_stage) dacc += double(two);   // (a lone last stage left its sum in `two`)
             issue(g + kStages, pipe[s]);
           }
         }
@@ -579,8 +576,7 @@ __global__ __launch_bounds__(NT, kTruncWavesPerSimd) void truncate_kernel(const 
         d[1] = neg_inf_vec<T>();
         if (v0 < nvec) d[0] = load_vec_stream(&rs.body[v0]);
         if (v1 < nvec) d[1] = load_vec_stream(&rs.body[v1]);
-        process_pair(d[0], d[1], v0, v1);
-        flush();
+        dacc += double(process_pair(d[0], d[1], v0, v1));
       }
       expand_ring<T>(ring, ring_vidx, wave_cnt < kRing ? wave_cnt : kRing, tau0, head, cand, p.sort_cap, sh);
       if (lost && lane == 0) sh.overflow = 1;
@@ -588,13 +584,12 @@ __global__ __launch_bounds__(NT, kTruncWavesPerSimd) void truncate_kernel(const 
       if (tid < n_edge) {
         const int64_t edge_i = edge_index<T>(rs, tid);
         const float edge_v = load_elem<T>(row, edge_i);
-        acc0 += fast_exp2(__builtin_fmaf(edge_v, k2, neg_c));
+        dacc += double(fast_exp2(__builtin_fmaf(edge_v, k2, neg_c)));
         if (edge_v > tau0) {
           const int pos = atomicAdd(&sh.cand_count, 1);
           if (pos < p.sort_cap) cand[pos] = make_cand(edge_v, uint32_t(edge_i));
         }
       }
-      flush();
       z_c = block_sum_f64<NW>(dacc, sh.red);
       __syncthreads();
       n_cand = sh.cand_count;

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
   if constexpr (ExpTab<T>::kHas && !ExpTab<T>::kSampled) {
     if (p.use_table) {
       table = reinterpret_cast<double*>(dyn_lds);
-      build_exp_table<T>(table, p.rT, kResThreads);
+      build_exp_table<T>(table, p.rT, kResThreads, 0);      // the second half: behind the first requests of the sweep
     }
   }
   int j0 = f0 != 1 ? lane : p.gamma;
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
     // kernel A has looked at a sample of the row (the bonus row it has not seen: the table is tried)
     if (p.use_table && !(residual && (p.row_status[b * p.gamma + jstar] & kRowTablePoor))) {
       table = reinterpret_cast<double*>(dyn_lds);
-      build_exp_table<T>(table, p.rT, kResThreads);
+      build_exp_table<T>(table, p.rT, kResThreads, 0);
     }
   }
   // the decision at that position, from the lane that holds it (a position beyond the first 64 is read again)
@@ -273,7 +273,8 @@ __global__ __launch_bounds__(kResThreads) void verify_resample_kernel(const Veri
         uint4 d[kSegVecs], dn[kSegVecs];
         int cur = wave;
         request(cur, d);
-        __syncthreads();                    // the table is complete (the requests travel meanwhile)
+        build_exp_table<T>(table, p.rT, kResThreads, 1);    // the table's second half, while the requests travel
+        __syncthreads();                    // the table is complete
         // the first run apart: behind it the set entry's target logit is requested, whose index has arrived
         // by then
         int nxt = next();
