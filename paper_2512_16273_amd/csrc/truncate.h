@@ -22,8 +22,13 @@ namespace tslt {
 constexpr int kTruncThreads = 256;   // threads of a truncate workgroup (one row each)
 constexpr int kBatch = 4;        // tiles of the threshold sample, taken at equal distances over the row
 constexpr int kGroup = 2;        // tiles (one 16-byte vector per thread each) in a stage of the pass's pipeline
-constexpr int kStages = 2;       // stages in flight per thread during the pass
-constexpr int kTruncWavesPerSimd = 8;   // asked of the compiler: 64 registers, eight workgroups per compute unit
+// The kernel comes in two shapes.  "Wide": two stages in flight per thread and eight waves per SIMD asked of the
+// compiler (64 registers), so that eight workgroups share a compute unit; for launches whose LDS footprint
+// allows that many (k_cap of a few hundred).  "Deep": four stages in flight and four waves per SIMD; for the
+// launches whose candidate arrays leave room for fewer workgroups (k_cap 1024: three per compute unit), which
+// then need more requests in flight each to keep the memory busy.
+constexpr int kStagesWide = 2, kWavesWide = 8;
+constexpr int kStagesDeep = 4, kWavesDeep = 4;
 constexpr int kRing = 96;      // vectors a wave can park
 constexpr int kRingExpand = 58; // expanded when it holds more than this: one pass of 64 lanes, nearly all busy
 
@@ -363,8 +368,8 @@ __device__ __forceinline__ float vec_max8(const float (&v)[8]) {
 template <> __device__ __forceinline__ float vec_max<Bf16>(const float (&v)[8]) { return vec_max8(v); }
 template <> __device__ __forceinline__ float vec_max<F16>(const float (&v)[8]) { return vec_max8(v); }
 
-template <typename T, int NT>
-__global__ __launch_bounds__(NT, kTruncWavesPerSimd) void truncate_kernel(const TruncateParams p) {
+template <typename T, int NT, int kStages, int kWavesPerSimd>
+__global__ __launch_bounds__(NT, kWavesPerSimd) void truncate_kernel(const TruncateParams p) {
   constexpr int E = ElemTraits<T>::kPerVec;
   constexpr int NW = NT / 64;
   static_assert(kBatch == 4, "the sample tiles are handled as two pairs");

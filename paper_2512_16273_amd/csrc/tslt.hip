@@ -115,6 +115,13 @@ hipError_t scratch_on_current_device(void** out) {
 
 constexpr int kLargeLds = int(kMaxLds - 4096);
 
+// The two shapes of the truncation kernel for one element type (see truncate.h).
+template <typename T, int NT, bool kWide> struct TruncKernel {
+  static constexpr auto fn = kWide ? &tslt::truncate_kernel<T, NT, tslt::kStagesWide, tslt::kWavesWide>
+                                   : &tslt::truncate_kernel<T, NT, tslt::kStagesDeep, tslt::kWavesDeep>;
+  hipError_t allow(int bytes) const { return tslt::allow_dynamic_lds<fn>(bytes); }
+};
+
 }  // namespace
 
 extern "C" {
@@ -174,16 +181,24 @@ static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_
   const bool big_lds = lds + sizeof(tslt::TruncateShared) > 48 * 1024;
   (void)ws; (void)ws_bytes;
   const dim3 grid{unsigned(rows)}, block{unsigned(NT)};
-  if (dt == TSLT_BF16) {
-    if (big_lds && (e = tslt::allow_dynamic_lds<&tslt::truncate_kernel<tslt::Bf16, NT>>(kLargeLds)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
-    hipLaunchKernelGGL((tslt::truncate_kernel<tslt::Bf16, NT>), grid, block, lds, s, p);
-  } else if (dt == TSLT_F16) {
-    if (big_lds && (e = tslt::allow_dynamic_lds<&tslt::truncate_kernel<tslt::F16, NT>>(kLargeLds)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
-    hipLaunchKernelGGL((tslt::truncate_kernel<tslt::F16, NT>), grid, block, lds, s, p);
-  } else {
-    if (big_lds && (e = tslt::allow_dynamic_lds<&tslt::truncate_kernel<float, NT>>(kLargeLds)) != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
-    hipLaunchKernelGGL((tslt::truncate_kernel<float, NT>), grid, block, lds, s, p);
-  }
+  // eight workgroups of this footprint on a compute unit: the wide shape; else the deep one
+  const bool wide = 8 * (lds + sizeof(tslt::TruncateShared) + 256) <= kMaxLds;
+  auto launch = [&](auto kernel_wide, auto kernel_deep) -> hipError_t {
+    if (wide) {
+      hipLaunchKernelGGL(kernel_wide.fn, grid, block, lds, s, p);
+      return hipSuccess;
+    }
+    if (big_lds) {
+      const hipError_t err = kernel_deep.allow(kLargeLds);
+      if (err != hipSuccess) return err;
+    }
+    hipLaunchKernelGGL(kernel_deep.fn, grid, block, lds, s, p);
+    return hipSuccess;
+  };
+  if (dt == TSLT_BF16) e = launch(TruncKernel<tslt::Bf16, NT, true>{}, TruncKernel<tslt::Bf16, NT, false>{});
+  else if (dt == TSLT_F16) e = launch(TruncKernel<tslt::F16, NT, true>{}, TruncKernel<tslt::F16, NT, false>{});
+  else e = launch(TruncKernel<float, NT, true>{}, TruncKernel<float, NT, false>{});
+  if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
   if ((e = hipGetLastError()) != hipSuccess) return hip_fail(e, "tslt_truncate launch");
   return TSLT_OK;
 }
