@@ -180,7 +180,7 @@ class ChainPlan:
         par = dict(sequences=0, positions=0, exact_index_sets=0, exact_draft_tokens=0, exact_accept_len=0, exact_tokens=0,
                    accept_near_ties=0, accept_near_tie_mismatches=0, top_rho_near_ties=0, top_rho_near_tie_mismatches=0,
                    cdf_edge_near_ties=0, mc_amp_near_ties=0, exact_path_rows=0, unexplained_mismatches=0,
-                   max_rel_err_prob=0.0, max_rel_err_ratio=0.0)
+                   max_rel_err_prob=0.0, max_rel_err_mass=0.0, max_rel_err_ratio=0.0)
         for (b, tr, smp, vr, _, _) in r1 + r2:
             par["sequences"] += 1
             par["positions"] += G
@@ -197,6 +197,8 @@ class ChainPlan:
                     c = int(tr["count"][jj])
                     rel = np.max(np.abs(g_tr["prob"][r, :c] - tr["prob"][jj, :c]) / tr["prob"][jj, :c]) if c else 0.0
                     par["max_rel_err_prob"] = max(par["max_rel_err_prob"], float(rel))
+                    if tr["mass"][jj] > 0:
+                        par["max_rel_err_mass"] = max(par["max_rel_err_mass"], float(abs(g_tr["mass"][r] - tr["mass"][jj]) / tr["mass"][jj]))
                     par["exact_draft_tokens"] += int(g_tr["token"][r, 0] == smp["token"][jj, 0])
                     if g_tr["token"][r, 0] != smp["token"][jj, 0]:
                         par["unexplained_mismatches"] += 1
@@ -229,6 +231,7 @@ class ChainPlan:
             else:
                 par["unexplained_mismatches"] += 1
         par["max_rel_err_prob"] = float(f"{par['max_rel_err_prob']:.3g}")
+        par["max_rel_err_mass"] = float(f"{par['max_rel_err_mass']:.3g}")
         par["max_rel_err_ratio"] = float(f"{par['max_rel_err_ratio']:.3g}")
         par["note"] = ("GPU outputs of the sequences the oracle was timed on; index sets, draft tokens, accepted lengths and emitted "
                        "tokens compared bit for bit; near-tie classes: |u - min(1, p/q)| < 1e-6, Top-rho boundary within 1e-6 of Z, "
