@@ -20,7 +20,7 @@
  *   - Data-dependent problems never abort.  They set bits in the optional per-row / per-sequence
  *     `status` array (TSLT_ROW_*) and give the defined fallback (count 0, token -1).
  *   - Logit rows are row-major with `row_stride` elements between rows; any alignment of the element
- *     type is accepted.  dtype is fp32, bf16 or binary16 (16-bit elements are widened exactly to fp32 on load).
+ *     type is accepted.  A row must be shorter than 4 GiB, and V below 2^31 (TSLT_ERR_UNSUPPORTED otherwise).  dtype is fp32, bf16 or binary16 (16-bit elements are widened exactly to fp32 on load).
  *   - Temperature (not in the paper): s = fl32(z * fl32(1/T)), one fp32 multiplication per logit.
  *     The SCALED values are what a truncated set carries, so the server needs no draft-side
  *     parameter: q_hat is the plain softmax of the received values.  T must be > 0.

@@ -145,6 +145,24 @@ __device__ __forceinline__ uint4 load_vec(const uint4* p) {
   return make_uint4(r.x, r.y, r.z, r.w);
 }
 
+// A row's aligned body as a buffer: 16-byte loads through a resource descriptor take the row's base and size
+// from scalar registers, a per-thread byte offset that never changes (lane * 16) from a vector register and
+// the moving part of the address from a scalar one, so that a streaming loop spends no vector instruction on
+// addresses; a load that reaches past the body's end returns zeros instead of faulting (the hardware checks
+// the range), and the loops give such vectors the value they need afterwards.  The body must be below 4 GiB.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_buffer(const uint4* body, uint32_t nvec) {
+  // (third dword: raw buffer of 32-bit data, the setting of the GFX9 family)
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4*>(body), 0, int(nvec * 16u), 0x00020000);
+}
+__device__ __forceinline__ uint4 buffer_load_vec_stream(__amdgpu_buffer_rsrc_t r, uint32_t lane_bytes, uint32_t wave_bytes) {
+  u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, int(lane_bytes), int(wave_bytes), 2);      // 2: nontemporal
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint4 buffer_load_vec(__amdgpu_buffer_rsrc_t r, uint32_t lane_bytes, uint32_t wave_bytes) {
+  u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, int(lane_bytes), int(wave_bytes), 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // max of three without the NaN-quieting moves the compiler adds around fmaxf (NaNs are found by other means)
 __device__ __forceinline__ float max3f(float a, float b, float c) {
   float r;

@@ -207,16 +207,14 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
   constexpr int U = kAccVecs;
   const uint32_t n_full = uint32_t(rs.nvec / (U * kBlock));      // batches of U complete tiles
   uint4 pipe[kAccDepth][U];
-  // Every request of the pipeline is unconditional: a vector past the row's end is read from the row's
-  // last vector instead and never used.  With conditional requests the number of loads in flight is not
-  // known where a wait is placed, and each wait for one batch waits for all of them.
-  const uint32_t last_vec = rs.nvec > 0 ? uint32_t(rs.nvec - 1) : 0u;
+  // Every request of the pipeline is unconditional: one past the row's end comes back as zeros and is never
+  // used.  With conditional requests the number of loads in flight is not known where a wait is placed, and
+  // each wait for one batch waits for all of them.
+  const __amdgpu_buffer_rsrc_t body = row_buffer(rs.body, uint32_t(rs.nvec));
+  const uint32_t lane_bytes = uint32_t(tid) * 16u;
   auto issue = [&](uint32_t b, uint4 (&q)[U]) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t vi = b * (U * kBlock) + u * kBlock + tid;
-      q[u] = load_vec_stream(rs.body + (vi < last_vec ? vi : last_vec));
-    }
+    for (int u = 0; u < U; ++u) q[u] = buffer_load_vec_stream(body, lane_bytes, (b * U + u) * (kBlock * 16u));
   };
   if (n_full > 0) {
 #pragma unroll

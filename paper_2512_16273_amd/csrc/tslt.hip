@@ -44,6 +44,8 @@ int hip_fail(hipError_t e, const char* what) {
 
 bool valid_dtype(tslt_dtype dt) { return dt == TSLT_F32 || dt == TSLT_BF16 || dt == TSLT_F16; }
 int elem_bytes(tslt_dtype dt) { return dt == TSLT_F32 ? 4 : 2; }
+// a row is addressed with 32-bit byte offsets from its start
+bool row_too_long(int64_t V, tslt_dtype dt) { return V > 0x7FFFFFFF || V * elem_bytes(dt) >= (int64_t(1) << 32); }
 
 // fl32(1/T), the one scaling constant every side derives the same way
 float reciprocal_temperature(float T) { return float(1.0 / double(T)); }
@@ -152,7 +154,7 @@ static int truncate_impl(const void* logits, tslt_dtype dt, int64_t rows, int64_
                          void* ws, size_t ws_bytes, void* stream) {
   if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: unknown dtype %d", int(dt));
   if (rows < 0 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: bad shape rows=%lld V=%lld stride=%lld", (long long)rows, (long long)V, (long long)row_stride);
-  if (V > 0x7FFFFFFF || rows > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "tslt_truncate: V and rows must fit 31 bits");
+  if (row_too_long(V, dt) || rows > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "tslt_truncate: rows must fit 31 bits, a row 4 GiB");
   if (!(temperature > 0.0f) || !std::isfinite(temperature)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: temperature must be > 0");
   if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "tslt_truncate: k_cap must be in 1..%d", TSLT_MAX_K_CAP);
   if (top_k < 0 || !(top_p >= 0.0f)) return fail(TSLT_ERR_INVALID_ARG, "tslt_truncate: top_k and top_p must be >= 0");
@@ -389,7 +391,7 @@ int tslt_truncation_stats(const void* target_logits, tslt_dtype dt, int64_t rows
   const char* name = "tslt_truncation_stats";
   if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "%s: unknown dtype %d", name, int(dt));
   if (rows < 0 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "%s: bad shape", name);
-  if (V > 0x7FFFFFFF || rows > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: V and rows must fit 31 bits", name);
+  if (row_too_long(V, dt) || rows > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: rows must fit 31 bits, a row 4 GiB", name);
   if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "%s: temperature must be > 0", name);
   if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "%s: k_cap must be in 1..%d", name, TSLT_MAX_K_CAP);
   if (n_k < 1 || n_k > tslt::kMaxStatK) return fail(TSLT_ERR_UNSUPPORTED, "%s: between 1 and %d values of K", name, tslt::kMaxStatK);
@@ -421,7 +423,7 @@ int tslt_multicandidate_stats(const void* target_logits, tslt_dtype dt, int64_t 
   const char* name = "tslt_multicandidate_stats";
   if (!valid_dtype(dt)) return fail(TSLT_ERR_INVALID_ARG, "%s: unknown dtype %d", name, int(dt));
   if (rows < 0 || V <= 0 || row_stride < V) return fail(TSLT_ERR_INVALID_ARG, "%s: bad shape", name);
-  if (V > 0x7FFFFFFF || rows > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: V and rows must fit 31 bits", name);
+  if (row_too_long(V, dt) || rows > 0x7FFFFFFF) return fail(TSLT_ERR_UNSUPPORTED, "%s: rows must fit 31 bits, a row 4 GiB", name);
   if (!(target_temperature > 0.0f) || !std::isfinite(target_temperature)) return fail(TSLT_ERR_INVALID_ARG, "%s: temperature must be > 0", name);
   if (k_cap < 1 || k_cap > TSLT_MAX_K_CAP) return fail(TSLT_ERR_UNSUPPORTED, "%s: k_cap must be in 1..%d", name, TSLT_MAX_K_CAP);
   if (k < 1 || k > TSLT_MAX_BRANCH) return fail(TSLT_ERR_UNSUPPORTED, "%s: between 1 and %d candidates", name, TSLT_MAX_BRANCH);
