@@ -301,3 +301,34 @@ def test_verify_reports_a_malformed_received_set(tslt):
         assert tok[b, j] == -1 and np.all(tok[b, :j] == ref["tokens"][b, :j])
     P.compare_verify({k: v[[0, 4]] for k, v in out.items()},
                      {k: v[[0, 4]] for k, v in ref["verify"].items()}, label="untouched")
+
+
+def test_verify_long_chain(tslt):
+    """More draft positions than a wave has lanes: the first rejection is looked for beyond the first 64
+    decisions, and the status words of all positions up to it are collected."""
+    w = W.scaled(W.WORKLOADS["chain_topk"], B=4, V=3001, gamma=150, top_k=8, k_cap=8)
+    chain = W.make_chain(w, 23, DEV)
+    u_acc = chain["u_accept"].clone()
+    u_acc[0, :70] = 0.0            # sequence 0: the first 70 positions accept whatever the ratio is
+    u_acc[1, :] = 0.0              # sequence 1: everything accepted, the bonus row is sampled
+    u_acc[2, :130] = 0.0           # sequence 2: the first rejection lies in the third group of 64
+    chain["u_accept"] = u_acc
+    ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), w.T, w.top_k, w.top_p, w.k_cap,
+                         P.to_np(chain["u_sample"]), P.to_np(u_acc), P.to_np(chain["u_resample"]))
+    # sequence 3: a draft token outside its set far down the chain (its status bit has to reach the output)
+    toks = ref["tokens"].copy()
+    u3 = P.to_np(u_acc).copy()
+    u3[3, :100] = 0.0
+    toks[3, 90] = int(np.setdiff1d(np.arange(w.V), ref["q_idx"][3, 90])[0])
+    v = O.verify_chain(P.to_np(chain["target"]), w.T, ref["q_idx"], ref["q_logit"], ref["q_count"], toks, u3,
+                       P.to_np(chain["u_resample"]))
+    out = tslt.verify(chain["target"], w.T, t32(ref["q_idx"]), t32(ref["q_logit"]), t32(ref["q_count"]), t32(toks),
+                      t32(u3), chain["u_resample"])
+    staged = tslt.verify(chain["target"], w.T, t32(ref["q_idx"]), t32(ref["q_logit"]), t32(ref["q_count"]), t32(toks),
+                         t32(u3), chain["u_resample"], first_stage=5)
+    torch.cuda.synchronize()
+    assert v["accept_len"][0] >= 70 and v["accept_len"][1] == 150 and v["accept_len"][2] >= 130
+    assert v["accept_len"][3] == 90 and v["status"][3] & 4
+    print(P.compare_verify(out, v, label="long chain"), v["accept_len"])
+    for k in ("accept_len", "tokens", "status"):
+        assert torch.equal(out[k], staged[k]), k
