@@ -120,9 +120,10 @@ __global__ __launch_bounds__(kBlock, kAccWavesPerSimd) void multicandidate_stats
       reach *= 1.0 - beta;
     }
     if (Z > 0.0) {
+      const double inv_Z = 1.0 / Z;
 #pragma unroll
-      for (int q = 0; q < kSetPer; ++q) a_s[q] /= Z;
-      c /= Z;
+      for (int q = 0; q < kSetPer; ++q) a_s[q] *= inv_Z;
+      c *= inv_Z;
     } else {
       live = false;
     }

@@ -168,9 +168,10 @@ __device__ __forceinline__ int mcveri_node(const TreeParams& p, int64_t b, int n
       }
       const double Z = block_sum_f64<kWaves>(part, sh.red) + c * p_out;
       if (Z > 0.0) {
+        const double inv_Z = 1.0 / Z;
 #pragma unroll
-        for (int q = 0; q < kSetPer; ++q) a_s[q] /= Z;
-        c /= Z;
+        for (int q = 0; q < kSetPer; ++q) a_s[q] *= inv_Z;
+        c *= inv_Z;
       }
       if (p.wor && found) {
         // drawn without replacement: x leaves the urn and what is left is renormalised

@@ -656,7 +656,7 @@ __global__ __launch_bounds__(NT, kWavesPerSimd) void truncate_kernel(const Trunc
   // normaliser relative to the row maximum: fp32 tail rescaled to that reference + fp64 head
   double tail = z_c - head32;
   if (tail < 0.0) tail = 0.0;
-  const double Z = k_eff > 0 ? tail * exp2(double(c_ref) - double(v0) * double(p.k2)) + head64 : 0.0;
+  const double Z = k_eff > 0 ? tail * exp64((double(c_ref) - double(v0) * double(p.k2)) * 0.69314718055994530942) + head64 : 0.0;
 
   int count = k_eff;
   if (p.top_p > 0.0f && k_eff > 0) {
@@ -713,13 +713,14 @@ __global__ __launch_bounds__(NT, kWavesPerSimd) void truncate_kernel(const Trunc
   }
 
   const size_t out0 = size_t(row_i) * size_t(p.k_cap);
+  const double inv_total = 1.0 / p_total;        // one reciprocal instead of a division per entry
 #pragma unroll
   for (int r = 0; r < kMaxPer; ++r) {
     const int i = tid * per + r;
     if (r < per && i < k_eff && i < count) {
       p.out_idx[out0 + i] = int32_t(idx[r]);
       p.out_logit[out0 + i] = s32[r];
-      if (p.out_prob) p.out_prob[out0 + i] = float(pw[r] / p_total);
+      if (p.out_prob) p.out_prob[out0 + i] = float(pw[r] * inv_total);
     }
   }
   for (int i = count + tid; i < p.k_cap; i += NT) {
