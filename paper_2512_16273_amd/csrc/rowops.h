@@ -30,7 +30,7 @@ constexpr int kSetPer = 1024 / kBlock;              // set entries per thread (T
 constexpr int kRowBadSet = 8;      // TSLT_ROW_BAD_SET
 
 struct SegResult {       // one segment (or edge piece) of a row that is being sampled
-  double sum;            // sum of exp(s - smax) over the piece
+  double sum;            // sum of exp(s - smax) over the piece (edge pieces; a segment's mass is in its runs' sums)
   float smax;            // largest scaled logit of the piece (-inf if empty)
   int bad;               // NaN or +inf seen
 };
@@ -385,55 +385,79 @@ __device__ __forceinline__ void load_segment(const RowSplit& rs, int seg, uint4 
   }
 }
 
-// One segment with every term an fp64 exponential referenced to the segment's own maximum.
+// Segments seg0 .. seg0 + n_here - 1 of a row with every term an fp64 exponential referenced to its segment's
+// own maximum.  One barrier per segment (the four waves exchange their runs' maxima through LDS, two buffers in
+// turn), the next segment's vectors requested before the current one is worked on; every request is
+// unconditional (a vector past the row's end is read from the row's last vector and counts as -inf).
 template <typename T>
-__device__ __forceinline__ void sweep_segment_direct(const RowSplit& rs, int seg, bool check, float rT,
-                                                     SegResult* segs, double* subs, VerifyShared& sh) {
+__device__ __forceinline__ void sweep_segments_direct(const RowSplit& rs, int seg0, int n_here, bool check, float rT,
+                                                      SegResult* segs, double* subs, VerifyShared& sh) {
   constexpr int E = ElemTraits<T>::kPerVec;
-  uint4 d[kSegVecs];
-  load_segment<T>(rs, seg, d);
-  float vmax = -INFINITY;
-  int bad = 0;
-#pragma unroll
-  for (int i = 0; i < kSegVecs; ++i) {
-    float v[E];
-    unpack<T>(d[i], v);
-    if (check) {
-#pragma unroll
-      for (int e = 0; e < E; ++e) bad |= (v[e] != v[e] || v[e] == INFINITY) ? 1 : 0;
-    }
-#pragma unroll
-    for (int e = 0; e < E; e += 2) vmax = max3f(vmax, v[e], v[e + 1]);
-  }
-  vmax = block_max_f32<kWaves>(vmax, sh.red);
-  bad = __syncthreads_or(bad);
-  const float smax = __fmul_rn(vmax, rT);      // scaling is monotone: the largest s is at the largest t
-  double run = 0.0;
-  if (smax > -INFINITY && !bad) {
-    const double m = double(smax);
+  const int lane = lane_id(), wave = wave_id();
+  const uint32_t nvec = uint32_t(rs.nvec), last_vec = nvec - 1;       // nvec > 0: the row has segments
+  auto request = [&](int seg, uint4 (&q)[kSegVecs]) {
+    const uint32_t vbase = uint32_t(seg) * kSegVecsTotal + wave * kRunVecs + lane;
 #pragma unroll
     for (int i = 0; i < kSegVecs; ++i) {
+      const uint32_t vi = vbase + i * 64;
+      q[i] = load_vec(&rs.body[vi < last_vec ? vi : last_vec]);
+    }
+  };
+  uint4 d[kSegVecs], dn[kSegVecs];
+  request(seg0, d);
+  for (int k = 0; k < n_here; ++k) {
+    const int seg = seg0 + k;
+    request(k + 1 < n_here ? seg + 1 : seg, dn);
+    const uint32_t vbase = uint32_t(seg) * kSegVecsTotal + wave * kRunVecs + lane;
+    float vmax = -INFINITY;
+    int bad = 0;
+#pragma unroll
+    for (int i = 0; i < kSegVecs; ++i) {
+      if (vbase + i * 64 >= nvec) d[i] = neg_inf_vec<T>();
       float v[E];
       unpack<T>(d[i], v);
-      double s0 = 0.0, s1 = 0.0;
+      if (check) {
 #pragma unroll
-      for (int e = 0; e < E; e += 2) {            // -inf gives exactly 0
-        s0 += exp64(double(__fmul_rn(v[e], rT)) - m);
-        s1 += exp64(double(__fmul_rn(v[e + 1], rT)) - m);
+        for (int e = 0; e < E; ++e) bad |= (v[e] != v[e] || v[e] == INFINITY) ? 1 : 0;
       }
-      run += s0 + s1;
+#pragma unroll
+      for (int e = 0; e < E; e += 2) vmax = max3f(vmax, v[e], v[e + 1]);
     }
+    vmax = wave_max_f32(vmax);
+    bad = wave_or_i32(bad);
+    const int buf = (k & 1) * 8;
+    if (lane == 0) { sh.red.f[buf + wave] = vmax; sh.red.i[buf + wave] = bad; }
+    __syncthreads();
+    float seg_max = sh.red.f[buf];
+    int seg_bad = sh.red.i[buf];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) { seg_max = fmaxf(seg_max, sh.red.f[buf + w]); seg_bad |= sh.red.i[buf + w]; }
+    const float smax = __fmul_rn(seg_max, rT);      // scaling is monotone: the largest s is at the largest t
+    double run = 0.0;
+    if (smax > -INFINITY && !seg_bad) {
+      const double m = double(smax);
+#pragma unroll
+      for (int i = 0; i < kSegVecs; ++i) {
+        float v[E];
+        unpack<T>(d[i], v);
+        double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+        for (int e = 0; e < E; e += 2) {            // -inf gives exactly 0
+          s0 += exp64(double(__fmul_rn(v[e], rT)) - m);
+          s1 += exp64(double(__fmul_rn(v[e + 1], rT)) - m);
+        }
+        run += s0 + s1;
+      }
+    }
+    const double run_sum = wave_sum_f64(run);
+    if (lane == 0) {
+      subs[size_t(seg) * kSubChunks + wave] = run_sum;
+      if (wave == 0) { segs[1 + seg].sum = 0.0; segs[1 + seg].smax = smax; segs[1 + seg].bad = seg_bad; }
+    }
+#pragma unroll
+    for (int i = 0; i < kSegVecs; ++i) d[i] = dn[i];
   }
-  const double run_sum = wave_sum_f64(run);
-  __syncthreads();
-  if (lane_id() == 0) { subs[size_t(seg) * kSubChunks + wave_id()] = run_sum; sh.red.d[wave_id()] = run_sum; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double t = 0.0;
-    for (int w = 0; w < kWaves; ++w) t += sh.red.d[w];
-    segs[1 + seg].sum = t; segs[1 + seg].smax = smax; segs[1 + seg].bad = bad;
-  }
-  __syncthreads();
+  __syncthreads();      // the exchange buffers are free again
 }
 
 // Segments group*kGroupSegs .. +kGroupSegs-1 of a row (all 256 threads of a workgroup); group 0 also does
@@ -484,8 +508,7 @@ __device__ __forceinline__ void sweep_group(const void* row, const RowSplit& rs,
       __syncthreads();
     }
   }
-  if (direct)
-    for (int k = 0; k < n_here; ++k) sweep_segment_direct<T>(rs, seg0 + k, check, rT, segs, subs, sh);
+  if (direct) sweep_segments_direct<T>(rs, seg0, n_here, check, rT, segs, subs, sh);
   if (group == 0 && tid == 0) {
     // the two edge pieces (at most E-1 elements each)
     for (int piece = 0; piece < 2; ++piece) {
