@@ -10,7 +10,7 @@ node (truncation and the draws of its candidates in one launch), tslt_verify_tre
 Independent input sets are rotated so that the 256 MB Infinity Cache cannot serve repeats.
 
 Prints ONE JSON line: positions/s, the roofline of the dominant kernel measured with an event pair on
-the launch stream around that kernel in every fourth step of the timed region (an untimed pass with events at every boundary gives
+the launch stream around that kernel in every eighth step of the timed region (an untimed pass with events at every boundary gives
 the per-kernel breakdown first), the CPU oracle timed on a bounded sample (one thread, then all cores), and
 a parity report: the GPU's outputs for the very sequences the oracle was timed on, compared item by item,
 with the near-tie classes counted.
@@ -466,7 +466,7 @@ def main():
     ap.add_argument("--stats-sweep", action="store_true", help="print retained mass and acceptance rate against K, and the "
                     "multi-candidate rates, on rows of benchmark configurations 2 and 3 (no timing)")
     ap.add_argument("--no-events", action="store_true", help="time the steps without per-kernel events")
-    ap.add_argument("--event-every", type=int, default=4, help="the event pair around the dominant kernel is recorded in "
+    ap.add_argument("--event-every", type=int, default=8, help="the event pair around the dominant kernel is recorded in "
                     "every N-th step of the timed region")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="after the timed steps run N plain elementwise copies of 1 GiB (read 1 GiB, write 1 GiB): "
