@@ -332,3 +332,25 @@ def test_verify_long_chain(tslt):
     print(P.compare_verify(out, v, label="long chain"), v["accept_len"])
     for k in ("accept_len", "tokens", "status"):
         assert torch.equal(out[k], staged[k]), k
+
+
+@pytest.mark.parametrize("dtype,V", [("bf16", 3), ("bf16", 9), ("f16", 7), ("f32", 3), ("f32", 70), ("bf16", 130), ("f16", 2100)])
+def test_verify_tiny_vocabularies(tslt, dtype, V):
+    """Rows shorter than a 16-byte vector (everything is an edge element), of one or two vectors, of one run:
+    the sweep has no run, or fewer runs than the resampling workgroup has waves."""
+    K = min(V, 4)
+    w = W.scaled(W.WORKLOADS["chain_topk"], B=7, V=V, gamma=3, dtype=dtype, top_k=K, k_cap=K, zipf=0.5, sigma=1.0)
+    chain = W.make_chain(w, 29, DEV)
+    u_acc = chain["u_accept"].clone()
+    u_acc[0] = 0.0                                   # one sequence reaches the bonus row
+    chain["u_accept"] = u_acc
+    ref = P.oracle_chain(P.to_np(chain["draft"]), P.to_np(chain["target"]), w.T, w.top_k, w.top_p, w.k_cap,
+                         P.to_np(chain["u_sample"]), P.to_np(u_acc), P.to_np(chain["u_resample"]))
+    tr = tslt.truncate(chain["draft"], w.T, w.top_k, w.top_p, K, u=chain["u_sample"].view(-1, 1))
+    out = run_verify_from_oracle_inputs(tslt, w, chain, ref)
+    torch.cuda.synchronize()
+    t = P.compare_truncate({k: v for k, v in tr.items() if k not in ("token", "slot")}, chain["draft"].view(-1, V), w.T, w.top_k,
+                           w.top_p, K, label=f"tiny {dtype} {V}")
+    assert t["top_p_near_ties"] == 0 and np.array_equal(P.to_np(tr["token"]).reshape(w.B, w.gamma), ref["tokens"])
+    res = P.compare_verify(out, ref["verify"], label=f"tiny {dtype} {V}")
+    assert res["accept_near_ties"] == 0 and ref["verify"]["accept_len"][0] == w.gamma
