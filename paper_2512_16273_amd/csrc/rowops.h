@@ -118,7 +118,7 @@ template <typename T> __device__ __forceinline__ void build_exp_table(double* ta
 // both halves of a 32-bit word at once (16-bit lanes: rotate, saturating subtract, minimum).  An element
 // outside the table's domain reads a NaN entry, which shows in the sum: table_vec_sum_raw returns that NaN
 // (so that a caller can add several vectors up and look once), table_vec_redo evaluates a vector element by
-// element, and table_vec_sum is the two together.
+// element.
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 template <typename T>
 __device__ __forceinline__ double table_vec_sum_raw(const uint4& d, const double* table) {
@@ -170,13 +170,6 @@ __device__ __forceinline__ double table_vec_redo(const uint4& d, float rT, int& 
   }
   return s;
 }
-template <typename T>
-__device__ __forceinline__ double table_vec_sum(const uint4& d, const double* table, float rT, int& flags) {
-  double s = table_vec_sum_raw<T>(d, table);
-  if (s != s) s = table_vec_redo<T>(d, rT, flags);
-  return s;
-}
-
 // ---------------------------------------------------------------------------------------------
 // One pass over a target row: partial sums of exp2(t*k2 - c), c referenced to the largest target
 // logit found at the set's indices; then, in fp64 over the <= 1024 received entries, p at those
@@ -374,17 +367,6 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
 // ---------------------------------------------------------------------------------------------
 constexpr int kGroupSegs = 4;     // consecutive segments a workgroup takes at a time
 
-template <typename T>
-__device__ __forceinline__ void load_segment(const RowSplit& rs, int seg, uint4 (&d)[kSegVecs]) {
-  const int64_t vbase = int64_t(seg) * kSegVecsTotal + wave_id() * kRunVecs + lane_id();
-#pragma unroll
-  for (int i = 0; i < kSegVecs; ++i) {
-    const int64_t vi = vbase + i * 64;
-    d[i] = neg_inf_vec<T>();
-    if (vi < rs.nvec) d[i] = load_vec(&rs.body[vi]);
-  }
-}
-
 // Segments seg0 .. seg0 + n_here - 1 of a row with every term an fp64 exponential referenced to its segment's
 // own maximum.  One barrier per segment (the four waves exchange their runs' maxima through LDS, two buffers in
 // turn), the next segment's vectors requested before the current one is worked on; every request is
@@ -473,27 +455,45 @@ __device__ __forceinline__ void sweep_group(const void* row, const RowSplit& rs,
   bool direct = n_here > 0;
   if constexpr (ExpTab<T>::kHas) {
     if (table != nullptr && n_here > 0) {
+      // (every request unconditional: a vector past the row's end is read from the row's last vector and its
+      // sum dropped; the four vectors' look-ups of a lane go out together and one look at their total says
+      // whether a value was outside the table)
       int flags = 0;
+      const uint32_t nvec = uint32_t(rs.nvec), last_vec = nvec - 1;
+      auto request = [&](int seg, uint4 (&q)[kSegVecs]) {
+        const uint32_t vb = uint32_t(seg) * kSegVecsTotal + wave_id() * kRunVecs + lane_id();
+#pragma unroll
+        for (int i = 0; i < kSegVecs; ++i) {
+          const uint32_t vi = vb + i * 64;
+          q[i] = load_vec(&rs.body[vi < last_vec ? vi : last_vec]);
+        }
+      };
       uint4 d[kSegVecs], dn[kSegVecs];
-      load_segment<T>(rs, seg0, d);
+      request(seg0, d);
 #pragma unroll
       for (int k = 0; k < kGroupSegs; ++k) {
         if (k < n_here) {
-          if (k + 1 < n_here) load_segment<T>(rs, seg0 + k + 1, dn);
-          const int64_t vbase = int64_t(seg0 + k) * kSegVecsTotal + wave_id() * kRunVecs + lane_id();
-          double run = 0.0;
+          request(k + 1 < n_here ? seg0 + k + 1 : seg0 + k, dn);
+          const uint32_t vbase = uint32_t(seg0 + k) * kSegVecsTotal + wave_id() * kRunVecs + lane_id();
+          double sv[kSegVecs];
 #pragma unroll
-          for (int i = 0; i < kSegVecs; ++i)
-            if (vbase + i * 64 < rs.nvec) run += table_vec_sum<T>(d[i], table, rT, flags);
+          for (int i = 0; i < kSegVecs; ++i) sv[i] = table_vec_sum_raw<T>(d[i], table);
+#pragma unroll
+          for (int i = 0; i < kSegVecs; ++i) sv[i] = vbase + i * 64 < nvec ? sv[i] : 0.0;
+          double run = (sv[0] + sv[1]) + (sv[2] + sv[3]);
+          if (run != run) {
+            run = 0.0;
+#pragma unroll
+            for (int i = 0; i < kSegVecs; ++i)
+              if (vbase + i * 64 < nvec) run += sv[i] == sv[i] ? sv[i] : table_vec_redo<T>(d[i], rT, flags);
+          }
           const double run_sum = wave_sum_f64(run);
           if (lane_id() == 0) {
             subs[size_t(seg0 + k) * kSubChunks + wave_id()] = run_sum;
             sh.red.d[k * kWaves + wave_id()] = run_sum;
           }
-          if (k + 1 < n_here) {
 #pragma unroll
-            for (int i = 0; i < kSegVecs; ++i) d[i] = dn[i];
-          }
+          for (int i = 0; i < kSegVecs; ++i) d[i] = dn[i];
         }
       }
       flags = block_or_i32<kWaves>(flags, sh.red);      // its barriers also publish the run sums
