@@ -134,8 +134,9 @@ __global__ __launch_bounds__(kBlock, kAccWavesPerSimd) void verify_accept_kernel
 
 // ---------------------------------------------------------------------------------------------
 // Kernel B: one workgroup of 1024 threads per sequence.  All 16 waves sweep the row to be sampled (wave
-// w takes runs w, w + 16, ...; the run and segment sums stay in LDS), then waves 4..15 end and the first
-// four do the inverse CDF (finish_core) and write the sequence's outputs.
+// w takes run w and then whichever run is next; the run sums stay in LDS), every thread takes one entry of
+// the sequence's sparse set on the way, then waves 4..15 end and the first four do the inverse CDF
+// (finish_core) and write the sequence's outputs.
 // ---------------------------------------------------------------------------------------------
 constexpr int kResThreads = 1024;
 constexpr int kResWaves = kResThreads / 64;
