@@ -170,6 +170,19 @@ __device__ __forceinline__ double table_vec_redo(const uint4& d, float rT, int& 
   }
   return s;
 }
+// Three sums over the workgroup with one pair of barriers.
+template <int NW>
+__device__ __forceinline__ void block_sum3_f64(double& a, double& b, double& c, BlockScratch& s) {
+  static_assert(NW <= 4, "the partial sums are laid out for at most four waves");
+  a = wave_sum_f64(a); b = wave_sum_f64(b); c = wave_sum_f64(c);
+  __syncthreads();
+  if (lane_id() == 0) { s.d[wave_id()] = a; s.d[4 + wave_id()] = b; s.d[8 + wave_id()] = c; }
+  __syncthreads();
+  a = 0.0; b = 0.0; c = 0.0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) { a += s.d[w]; b += s.d[4 + w]; c += s.d[8 + w]; }
+}
+
 // ---------------------------------------------------------------------------------------------
 // One pass over a target row: partial sums of exp2(t*k2 - c), c referenced to the largest target
 // logit found at the set's indices; then, in fp64 over the <= 1024 received entries, p at those
@@ -341,9 +354,7 @@ __device__ __forceinline__ void eval_row_on_set(const void* row, const RowSplit&
       }
     }
   }
-  sum_e = block_sum_f64<kWaves>(sum_e, sh.red);
-  sum_t32 = block_sum_f64<kWaves>(sum_t32, sh.red);
-  sum_w = block_sum_f64<kWaves>(sum_w, sh.red);
+  block_sum3_f64<kWaves>(sum_e, sum_t32, sum_w, sh.red);
   if (sum_w != sum_w) { st |= kRowBadSet; ok = false; }
   double tail = z_c - sum_t32;
   if (tail < 0.0) tail = 0.0;
@@ -583,18 +594,6 @@ __device__ __forceinline__ void load_set_entries(const void* row, int64_t V, con
   }
 }
 
-// Three sums over the workgroup with one pair of barriers.
-template <int NW>
-__device__ __forceinline__ void block_sum3_f64(double& a, double& b, double& c, BlockScratch& s) {
-  a = wave_sum_f64(a); b = wave_sum_f64(b); c = wave_sum_f64(c);
-  __syncthreads();
-  if (lane_id() == 0) { s.d[wave_id()] = a; s.d[4 + wave_id()] = b; s.d[8 + wave_id()] = c; }
-  __syncthreads();
-  a = 0.0; b = 0.0; c = 0.0;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) { a += s.d[w]; b += s.d[4 + w]; c += s.d[8 + w]; }
-}
-
 // Returns the token (-1 if none) and ORs TSLT_ROW_* bits into st.  After m updates with the same q_hat
 // the distribution is c * p outside the set and a_i on it, where a and c follow the recursion
 // a <- max(0, a - q_hat) / Z, c <- c / Z, Z = sum(max(0, a - q_hat)) + c * p_out; in units of the row's
@@ -607,7 +606,6 @@ __device__ __forceinline__ void block_sum3_f64(double& a, double& b, double& c, 
 // the chosen run is found from one vector per thread.  Called by all kBlock threads of a workgroup.
 template <typename T>
 __device__ int finish_core(const FinishArgs& a, VerifyShared& sh, int& st, const SetEntries* pre = nullptr) {
-  static_assert(kWaves == 4, "block_sum3_f64 lays its partial sums out for four waves");
   constexpr int E = ElemTraits<T>::kPerVec;
   constexpr int kMaxPer = kSetPer;
   constexpr int kRun = kRunVecs * E;        // elements in a run
