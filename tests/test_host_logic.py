@@ -115,3 +115,10 @@ def test_exp64_header_matches_libm(tmp_path):
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
     m = re.search(r"max_ulp ([0-9.]+) edge (\d)", out)
     assert m and float(m.group(1)) < 1.5 and m.group(2) == "1", out
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build measures one GPU; asked for more, bench.py says so and exits before it touches a device."""
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
